@@ -1,0 +1,205 @@
+"""Seeded synthetic workloads for the batched IVF retrieval path.
+
+This module only *draws inputs*: Gaussian-mixture embeddings, their inverted-list
+grouping, user ids and query batches.  It holds none of the retrieval arithmetic
+(no similarity search, no probe selection, no k-selection) and is the one piece
+shared by the HIP path's tests/bench and the CPU oracle's tests.
+
+The paper's knowledge base (a TriviaQA-derived vector store of ~256 GB in 32
+partitions, Section 6.1 "Dataset and Models") is not available and its embedding
+model is not named, so these inputs stand in for it: same role (a chunk-embedding
+store far larger than a query batch, batched queries, small k), shapes taken
+from the benchmark configurations.
+
+Recipe (per configuration, master seed S):
+  * centroids  mu_c = g / |g|,  g ~ N(0, I_d)              (NumPy, stream 0)
+  * list sizes (len_0..len_{nlist-1}) ~ Multinomial(n, uniform)  (NumPy, stream 1)
+  * vectors of list c:  x = (mu_c + sigma * g) / |mu_c + sigma * g|, g ~ N(0, I_d),
+    drawn per *group* of GROUP consecutive lists so that any group can be
+    regenerated alone                                       (stream 2, group index)
+  * queries: component c ~ Uniform{0..nlist-1}, same formula (stream 3, batch index)
+  * user ids: a seeded permutation of 0..n-1 laid over the list-major order (stream 4)
+
+A vector's list is the mixture component it was drawn from.  With these sigmas the
+home centroid wins the arg-max inner product by more than ten standard deviations
+of the cross-component score, so this equals "assigned to its argmax-IP centroid";
+the tests check that equality with the oracle's assignment routine (all of C1,
+samples of the larger configurations) instead of trusting it.
+
+Two backends draw the normals: NumPy on the host (small configurations, usable
+without a GPU) and torch on the device (large ones; the bytes never visit the
+host).  They follow the same recipe but different random streams.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Iterator, Optional, Tuple
+
+import numpy as np
+
+GROUP = 64  # lists per generation group
+_MASTER = 250415302
+
+_STREAM_MEANS, _STREAM_SIZES, _STREAM_NOISE, _STREAM_QUERY, _STREAM_IDS = range(5)
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    n: int
+    d: int
+    nlist: int
+    sigma: float
+    storage: str          # "fp32" | "fp16"
+    nq: int
+    nprobe: int
+    k: int
+    seed: int
+    resident_list_frac: Optional[float] = None  # None = everything HBM-resident
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.storage == "fp32" else 2
+
+    @property
+    def ngroups(self) -> int:
+        return (self.nlist + GROUP - 1) // GROUP
+
+
+CONFIGS = {
+    "C1": Workload("C1", 100_000, 384, 256, 0.05, "fp32", 16, 8, 10, _MASTER + 0),
+    "C2": Workload("C2", 2_000_000, 768, 4096, 0.04, "fp32", 32, 32, 10, _MASTER + 1),
+    "C3": Workload("C3", 20_000_000, 768, 16384, 0.04, "fp16", 64, 64, 20, _MASTER + 2),
+    # same index and queries as C3 (first 8 of its 64), a quarter of the lists resident
+    "C4": Workload("C4", 20_000_000, 768, 16384, 0.04, "fp16", 8, 64, 20, _MASTER + 2,
+                   resident_list_frac=0.25),
+    "C5": Workload("C5", 100_000_000, 768, 65536, 0.04, "fp16", 128, 128, 100, _MASTER + 4),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A workload with some fields replaced (reduced sizes for quick tests)."""
+    return replace(w, **kw)
+
+
+def _rng(w: Workload, stream: int, index: int = 0) -> np.random.Generator:
+    return np.random.default_rng([w.seed, stream, index])
+
+
+def _torch_seed(w: Workload, stream: int, index: int) -> int:
+    ss = np.random.SeedSequence([w.seed, stream, index])
+    return int(ss.generate_state(1, dtype=np.uint64)[0] >> np.uint64(1))
+
+
+def centroids(w: Workload) -> np.ndarray:
+    """[nlist, d] float32 unit vectors: the mixture means, which are also the
+    coarse-quantiser centroids."""
+    g = _rng(w, _STREAM_MEANS).standard_normal((w.nlist, w.d))
+    g /= np.linalg.norm(g, axis=1, keepdims=True)
+    return np.ascontiguousarray(g.astype(np.float32))
+
+
+def list_offsets(w: Workload) -> np.ndarray:
+    """[nlist+1] int64 prefix sums of the multinomial list sizes."""
+    sizes = _rng(w, _STREAM_SIZES).multinomial(w.n, np.full(w.nlist, 1.0 / w.nlist))
+    off = np.zeros(w.nlist + 1, dtype=np.int64)
+    np.cumsum(sizes, out=off[1:])
+    return off
+
+
+def queries(w: Workload, batch: int = 0, nq: Optional[int] = None) -> np.ndarray:
+    """[nq, d] float32 unit query embeddings of batch number `batch`.  The first
+    rows of a batch do not depend on nq, so C4's 8 queries are C3's first 8."""
+    nq = w.nq if nq is None else nq
+    cen = centroids(w)
+    out = np.empty((nq, w.d), dtype=np.float32)
+    for i in range(nq):
+        rng = np.random.default_rng([w.seed, _STREAM_QUERY, batch, i])
+        comp = int(rng.integers(0, w.nlist))
+        g = rng.standard_normal(w.d).astype(np.float32)
+        x = cen[comp] + np.float32(w.sigma) * g
+        out[i] = x / np.linalg.norm(x)
+    return out
+
+
+def _group_rows(w: Workload, off: np.ndarray, group: int) -> Tuple[int, int, int, int]:
+    l0 = group * GROUP
+    l1 = min(w.nlist, l0 + GROUP)
+    return l0, l1, int(off[l0]), int(off[l1])
+
+
+def group_vectors_host(w: Workload, cen: np.ndarray, off: np.ndarray, group: int) -> np.ndarray:
+    """Row-major vectors of the lists of one group, list after list, in the
+    storage type (float32 or float16), drawn with NumPy."""
+    l0, l1, r0, r1 = _group_rows(w, off, group)
+    rows = r1 - r0
+    g = _rng(w, _STREAM_NOISE, group).standard_normal((rows, w.d), dtype=np.float32)
+    label = np.repeat(np.arange(l0, l1), np.diff(off[l0:l1 + 1]))
+    x = cen[label] + np.float32(w.sigma) * g
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    return x.astype(np.float16 if w.storage == "fp16" else np.float32)
+
+
+def group_vectors_device(w: Workload, cen_dev, off: np.ndarray, group_begin: int, group_end: int,
+                         device="cuda"):
+    """Same recipe on the GPU with torch's generator; returns a device tensor
+    [rows, d] covering groups [group_begin, group_end), list-major."""
+    import torch
+    parts = []
+    gen = torch.Generator(device=device)
+    for group in range(group_begin, group_end):
+        l0, l1, r0, r1 = _group_rows(w, off, group)
+        rows = r1 - r0
+        gen.manual_seed(_torch_seed(w, _STREAM_NOISE, group))
+        g = torch.randn((rows, w.d), generator=gen, device=device, dtype=torch.float32)
+        sizes = torch.from_numpy(np.diff(off[l0:l1 + 1])).to(device)
+        label = torch.repeat_interleave(torch.arange(l0, l1, device=device), sizes)
+        g.mul_(w.sigma).add_(cen_dev[label])
+        g.div_(torch.linalg.vector_norm(g, dim=1, keepdim=True))
+        parts.append(g.to(torch.float16) if w.storage == "fp16" else g)
+    return torch.cat(parts, dim=0) if len(parts) != 1 else parts[0]
+
+
+def user_ids_host(w: Workload) -> np.ndarray:
+    """[n] int64: the user id of the vector at each list-major position."""
+    return _rng(w, _STREAM_IDS).permutation(w.n).astype(np.int64)
+
+
+def user_ids_device(w: Workload, device="cuda"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(_torch_seed(w, _STREAM_IDS, 0))
+    return torch.randperm(w.n, generator=gen, device=device, dtype=torch.int64)
+
+
+def list_labels(off: np.ndarray) -> np.ndarray:
+    """[n] int32 list number of every list-major position."""
+    return np.repeat(np.arange(len(off) - 1, dtype=np.int32), np.diff(off))
+
+
+@dataclass
+class HostIndex:
+    """A whole index in host memory (small configurations)."""
+    w: Workload
+    centroids: np.ndarray   # [nlist, d] float32
+    vectors: np.ndarray     # [n, d] float32 or float16, list-major
+    ids: np.ndarray         # [n] int64
+    offsets: np.ndarray     # [nlist+1] int64
+
+
+def build_host_index(w: Workload) -> HostIndex:
+    cen = centroids(w)
+    off = list_offsets(w)
+    parts = [group_vectors_host(w, cen, off, g) for g in range(w.ngroups)]
+    vec = np.ascontiguousarray(np.concatenate(parts, axis=0))
+    return HostIndex(w, cen, vec, user_ids_host(w), off)
+
+
+def iter_device_chunks(w: Workload, cen_dev, off: np.ndarray, groups_per_chunk: int,
+                       device="cuda") -> Iterator[Tuple[int, int, "object"]]:
+    """Yields (list_begin, list_end, vectors[rows, d]) covering the index in
+    list order, a few groups at a time, so that a caller can hand the index to
+    the library without ever holding all of it."""
+    for g0 in range(0, w.ngroups, groups_per_chunk):
+        g1 = min(w.ngroups, g0 + groups_per_chunk)
+        yield g0 * GROUP, min(w.nlist, g1 * GROUP), group_vectors_device(w, cen_dev, off, g0, g1, device)
