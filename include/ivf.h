@@ -1,0 +1,189 @@
+/*
+ * ivf.h — C ABI of the MI355X (gfx950) batched IVF inner-product top-k retrieval
+ * library: the retrieval stage of a decoupled retrieve-then-generate RAG pipeline.
+ *
+ * The operation: for a batch of query embeddings, match them against the stored
+ * chunk embeddings by similarity search and return the k most relevant chunks per
+ * query (paper Section 2.2 "On-demand RAG Serving"; one batch per call, Section 2.3
+ * "Batch Scheduling"; top-k, Section 6.1 "Workloads"; results never approximated,
+ * Section 6.1 "Key Metrics").  Only part of the store needs to live in the fast
+ * memory tier; the rest is loaded on demand per retrieval batch (Section 4.2
+ * "Database partitions"; Section 5 "Lazy dynamic transfer") — here the fast tier is
+ * HBM and the slow tier is pinned host memory.  Index type and metric are fixed by
+ * the benchmark, not by the paper: IVF-Flat, inner product, given centroids.
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative ivf_status; it never aborts
+ *     and never throws.  ivf_last_error() gives a thread-local message for the last
+ *     failing call on the calling thread.
+ *   - "host or device" pointers are classified by the library itself.
+ *   - The library COPIES what it is given at upload; the caller keeps ownership of
+ *     its buffers and may free them when the call returns.
+ *   - One search (or upload, or budget change) at a time per index: calls on the
+ *     same index must not overlap.  Different indexes are independent.
+ *   - Limits: d a multiple of 8 and d <= 4096; 1 <= k <= 1024; 1 <= nprobe <= 1024
+ *     (nprobe above nlist is clamped to nlist); n < 2^32; nlist < 2^31.
+ *   - Ordering rule: best first by (score descending, user id ascending, upload
+ *     position ascending).  The GPU accumulates scores in fp32.
+ */
+#ifndef IVF_H
+#define IVF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ivf_index ivf_index; /* opaque, owned by the library */
+
+typedef enum {
+    IVF_OK = 0,
+    IVF_ERR_INVALID = -1,   /* null pointer, bad size, call out of sequence */
+    IVF_ERR_OOM_DEVICE = -2,
+    IVF_ERR_OOM_HOST = -3,  /* pinned host memory */
+    IVF_ERR_HIP = -4,       /* a HIP runtime call failed; message has hipGetErrorString */
+    IVF_ERR_LIMIT = -5      /* argument beyond a documented limit */
+} ivf_status;
+
+enum { IVF_FP32 = 0, IVF_FP16 = 1 };
+
+/* Creates an empty index bound to the current HIP device. */
+int ivf_index_create(ivf_index **out);
+
+/* Frees device and pinned-host memory of the index.  NULL is allowed. */
+void ivf_index_destroy(ivf_index *idx);
+
+/*
+ * ivf_index_upload — hand a complete IVF-Flat index to the library (data preparation,
+ * not part of the timed path).  Vectors are ALREADY grouped by inverted list.
+ *   d             embedding dimension
+ *   nlist         number of inverted lists (= number of centroids)
+ *   n             number of stored vectors
+ *   centroids     [nlist, d] fp32 row-major, host or device
+ *   vectors       [n, d] row-major in list order, fp32 or IEEE binary16 per `dtype`,
+ *                 host or device
+ *   ids           [n] user ids in the same order, host or device
+ *   list_offsets  [nlist+1], list j owns rows [list_offsets[j], list_offsets[j+1]);
+ *                 list_offsets[0] = 0, list_offsets[nlist] = n; host or device
+ * The library re-lays the vectors out for its scan kernel.  Everything starts
+ * HBM-resident.  Replaces any previous content of the index.
+ */
+int ivf_index_upload(ivf_index *idx, int d, int64_t nlist, int64_t n, const float *centroids,
+                     const void *vectors, int dtype, const int64_t *ids,
+                     const int64_t *list_offsets);
+
+/*
+ * The same upload in pieces, for indexes too large for the caller to hold next to
+ * the library's copy: begin (sizes, centroids, list table), then any number of
+ * upload_lists calls that together cover lists [0, nlist) in ascending order without
+ * gaps, then end (builds the id tables).  `vectors`/`ids` of a piece cover rows
+ * [list_offsets[list_begin], list_offsets[list_end]) only.
+ */
+int ivf_index_upload_begin(ivf_index *idx, int d, int64_t nlist, int64_t n,
+                           const float *centroids, int dtype, const int64_t *list_offsets);
+int ivf_index_upload_lists(ivf_index *idx, int64_t list_begin, int64_t list_end,
+                           const void *vectors, const int64_t *ids);
+int ivf_index_upload_end(ivf_index *idx);
+
+/*
+ * ivf_set_device_budget — bytes of HBM the list data may occupy (the analogue of the
+ * number of resident database partitions, Section 4.2).  Lists are ranked by
+ * (length descending, list number ascending) and stay HBM-resident, in that order,
+ * while their padded size still fits in `bytes`; all others are moved to pinned host
+ * memory and are streamed to the GPU per search batch.  INT64_MAX (or anything at
+ * least the index size) makes everything resident again.  Results of ivf_search do
+ * not depend on the budget.  Blocks until the move is done.  On failure the previous
+ * placement is kept.
+ */
+int ivf_set_device_budget(ivf_index *idx, int64_t bytes);
+
+/*
+ * ivf_search — batched top-k inner-product search.
+ *   queries     [nq, d] fp32 row-major, DEVICE pointer
+ *   nq          batch size (0 is allowed and does nothing)
+ *   nprobe      inverted lists scanned per query (the nprobe largest <q, centroid>,
+ *               ties to the smaller list number)
+ *   k           results per query
+ *   out_ids     [nq, k] int64 DEVICE pointer: user ids, best first; -1 where fewer
+ *               than k candidates exist
+ *   out_scores  [nq, k] fp32 DEVICE pointer: inner products; -inf where padded
+ *   stream      hipStream_t (NULL = default stream).  Work is enqueued on it; the
+ *               outputs are valid once the caller has synchronised it.  When every
+ *               list is HBM-resident and the scratch buffers are already large
+ *               enough the call does not block; with host-resident lists it blocks
+ *               until their copies have been issued (it uses one internal side
+ *               stream for them and joins it to `stream` with events).
+ * The first call (and any call with a larger nq*nprobe or k than before) allocates
+ * scratch memory; later calls reuse it.
+ */
+int ivf_search(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int k,
+               int64_t *out_ids, float *out_scores, void *stream);
+
+/* Thread-local message of the last error on this thread ("" if none). */
+const char *ivf_last_error(void);
+
+/* ---- introspection (evidence and tests; not on the hot path) ---- */
+
+typedef struct {
+    int32_t d, dtype;
+    int64_t nlist, n;
+    int64_t max_list_len;
+    int64_t index_bytes;        /* padded list data, device + host */
+    int64_t device_list_bytes;  /* padded list data resident in HBM */
+    int64_t host_list_bytes;    /* padded list data in pinned host memory */
+    int64_t resident_lists;
+    int64_t scratch_bytes;      /* search scratch currently allocated */
+} ivf_info;
+int ivf_get_info(ivf_index *idx, ivf_info *out);
+
+/* Probed lists of the last search, best first: [nq, nprobe] int32 DEVICE pointer,
+   copied on `stream`. */
+int ivf_debug_last_probes(ivf_index *idx, int32_t *out_lists, void *stream);
+
+/* Coarse scores <q, centroid> of the last search: [nq, nlist] fp32 DEVICE pointer,
+   copied on `stream` (stage-wise parity of the coarse quantiser). */
+int ivf_debug_last_coarse(ivf_index *idx, float *out_scores, void *stream);
+
+/* Reads list `list` back from the library's own storage (HBM or pinned host) into
+   row-major HOST buffers: out_vectors [len, d] in the index dtype, out_ids [len].
+   Either may be NULL.  Returns the list length through *len. */
+int ivf_debug_read_list(ivf_index *idx, int64_t list, void *out_vectors, int64_t *out_ids,
+                        int64_t *len);
+
+typedef struct {
+    int64_t unique_lists;        /* distinct lists probed by the batch */
+    int64_t pairs;               /* (query, list) pairs = nq * nprobe */
+    int64_t scanned_vectors;     /* sum of len over unique probed lists */
+    int64_t scan_bytes;          /* the same in bytes of stored data (unpadded) */
+    int64_t scan_bytes_resident; /* part of scan_bytes read from HBM-resident lists */
+    int64_t scan_bytes_streamed; /* part copied from pinned host memory for this batch */
+    int64_t scan_items;          /* 64-vector work items launched */
+} ivf_search_stats;
+/* Statistics of the last search; synchronises the stream it ran on. */
+int ivf_last_search_stats(ivf_index *idx, ivf_search_stats *out);
+
+/* Stage timing with HIP events on the search's own stream.  When enabled, every
+   search records events around its stages; ivf_get_stage_ms synchronises and returns
+   the last search's times in milliseconds. */
+enum {
+    IVF_STAGE_COARSE = 0,   /* centroid GEMM + tile maxima */
+    IVF_STAGE_PROBE = 1,    /* top-nprobe selection */
+    IVF_STAGE_REGROUP = 2,  /* list-major regrouping + work plan */
+    IVF_STAGE_SCAN = 3,     /* scan of HBM-resident lists (one kernel launch) */
+    IVF_STAGE_STREAM = 4,   /* host-resident lists: copies + their scans (0 if none) */
+    IVF_STAGE_SELECT = 5,   /* final k-selection */
+    IVF_STAGE_TOTAL = 6,
+    IVF_NUM_STAGES = 7
+};
+int ivf_set_timing(ivf_index *idx, int enable);
+int ivf_get_stage_ms(ivf_index *idx, float *ms /* [IVF_NUM_STAGES] host */);
+
+/* Tuning knobs for experiments (launch shape of the scan kernel etc.); unknown names
+   return IVF_ERR_INVALID.  Defaults are the tuned values. */
+int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVF_H */

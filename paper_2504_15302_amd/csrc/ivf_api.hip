@@ -1,0 +1,1003 @@
+// Host side of the IVF retrieval library: index storage, placement between HBM and
+// pinned host memory, and the per-search launch sequence.  Exports the C ABI declared
+// in include/ivf.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "../../include/ivf.h"
+#include "ivf_coarse.h"
+#include "ivf_device.h"
+#include "ivf_regroup.h"
+#include "ivf_scan.h"
+#include "ivf_select.h"
+
+extern "C" int ivf_internal_sort_pairs(const int64_t* keys_in, int64_t* keys_out,
+                                       const uint32_t* vals_in, uint32_t* vals_out, size_t n,
+                                       hipStream_t stream);
+
+namespace {
+
+using namespace ivf;
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) {                                                            \
+            (void)hipGetLastError();                                                       \
+            return fail(e_ == hipErrorOutOfMemory ? IVF_ERR_OOM_DEVICE : IVF_ERR_HIP,      \
+                        "%s failed: %s", #expr, hipGetErrorString(e_));                    \
+        }                                                                                  \
+    } while (0)
+
+bool is_device_ptr(const void* p) {
+    hipPointerAttribute_t a;
+    hipError_t e = hipPointerGetAttributes(&a, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();   // plain host memory is reported as an error
+        return false;
+    }
+    return a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged ||
+           a.type == hipMemoryTypeUnified;
+}
+
+template <class T>
+void dfree(T*& p) {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+}
+
+struct Scratch {
+    size_t cap_q_nlist = 0, cap_q_ntile = 0, cap_pairs = 0, cap_blocks = 0, cap_stream_items = 0;
+    int64_t cap_nlist = 0;
+    float* S = nullptr;
+    float* tmax = nullptr;
+    int32_t* probes = nullptr;
+    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16]
+    uint32_t* pair_start = nullptr;
+    uint32_t* sblk_start = nullptr;
+    uint32_t* item_start = nullptr;
+    unsigned long long* counters = nullptr;
+    uint32_t* pair_flat = nullptr;
+    uint32_t* pair_q = nullptr;
+    uint32_t* pair_of_probe = nullptr;
+    ScanItem* items = nullptr;
+    ScanItem* stream_items = nullptr;
+    float* scores = nullptr;
+    float* bmax = nullptr;
+    // pinned host mirrors for the streamed path
+    int32_t* h_probes = nullptr;
+    size_t h_probes_cap = 0;
+    ScanItem* h_items = nullptr;
+    size_t h_items_cap = 0;
+    unsigned long long* h_counters = nullptr;
+    size_t bytes = 0;
+};
+
+constexpr int kMaxStage = 8;
+
+}  // namespace
+
+struct ivf_index {
+    int device = 0;
+    int cus = 256;
+    bool uploading = false, ready = false;
+    int d = 0, dtype = 0, es = 4;
+    int64_t nlist = 0, n = 0, next_list = 0;
+    size_t row_bytes = 0, block_bytes = 0;
+    int64_t total_blocks = 0, max_len = 0;
+    std::vector<int64_t> offsets, blk_off;
+    std::vector<int32_t> len, nblk;
+    std::vector<int64_t> top_nblk_prefix;       // prefix sums of nblk sorted descending
+    std::vector<const char*> dev_ptr, host_ptr; // per list: where its blocks live
+    // device tables
+    float* d_centroids = nullptr;
+    int64_t* d_offsets = nullptr;
+    int64_t* d_blk_off = nullptr;
+    int32_t* d_len = nullptr;
+    int32_t* d_nblk = nullptr;
+    const void** d_list_ptr = nullptr;
+    int64_t* d_ids_pos = nullptr;      // only while uploading
+    int64_t* d_id_sorted = nullptr;
+    uint32_t* d_rank_of_pos = nullptr;
+    // list data
+    char* d_arena = nullptr;
+    size_t d_arena_bytes = 0;
+    char* h_arena = nullptr;
+    size_t h_arena_bytes = 0;
+    int64_t resident_lists = 0;
+    // streaming of host-resident lists
+    hipStream_t side = nullptr;
+    char* stage[kMaxStage] = {};
+    hipEvent_t stage_ready[kMaxStage] = {}, stage_free[kMaxStage] = {};
+    bool stage_used[kMaxStage] = {};
+    size_t stage_bytes = 0;
+    int nstage = 0;
+    hipEvent_t ev_probes = nullptr, ev_done = nullptr;
+    bool done_recorded = false;
+    // search state
+    Scratch sc;
+    int last_nq = 0, last_nprobe = 0;
+    hipStream_t last_stream = nullptr;
+    bool last_offload = false;
+    ivf_search_stats last_stats = {};
+    bool timing = false;
+    hipEvent_t ev[IVF_NUM_STAGES + 1] = {};
+    bool ev_valid = false;
+    // options
+    int64_t opt_scan_mode = 0, opt_scan_unroll = 8, opt_scan_wgs_per_cu = 2, opt_stage_mb = 64,
+            opt_nstage = 3;
+};
+
+namespace {
+
+void free_scratch(Scratch& s) {
+    dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
+    dfree(s.sblk_start); dfree(s.item_start); dfree(s.counters); dfree(s.pair_flat);
+    dfree(s.pair_q); dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
+    dfree(s.scores); dfree(s.bmax);
+    if (s.h_probes) (void)hipHostFree(s.h_probes);
+    if (s.h_items) (void)hipHostFree(s.h_items);
+    if (s.h_counters) (void)hipHostFree(s.h_counters);
+    s = Scratch();
+}
+
+void free_staging(ivf_index* x) {
+    for (int i = 0; i < kMaxStage; ++i) {
+        if (x->stage[i]) (void)hipFree(x->stage[i]);
+        x->stage[i] = nullptr;
+        x->stage_used[i] = false;
+    }
+    x->nstage = 0;
+    x->stage_bytes = 0;
+}
+
+void free_index_data(ivf_index* x) {
+    dfree(x->d_centroids); dfree(x->d_offsets); dfree(x->d_blk_off); dfree(x->d_len);
+    dfree(x->d_nblk); dfree(x->d_list_ptr); dfree(x->d_ids_pos); dfree(x->d_id_sorted);
+    dfree(x->d_rank_of_pos); dfree(x->d_arena);
+    if (x->h_arena) (void)hipHostFree(x->h_arena);
+    x->h_arena = nullptr;
+    x->d_arena_bytes = x->h_arena_bytes = 0;
+    free_staging(x);
+    free_scratch(x->sc);
+    x->ready = x->uploading = false;
+    x->resident_lists = 0;
+}
+
+template <class T>
+int dalloc(T*& p, size_t count, size_t& total) {
+    dfree(p);
+    size_t bytes = std::max<size_t>(count * sizeof(T), 256);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p), bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        p = nullptr;
+        return fail(IVF_ERR_OOM_DEVICE, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    }
+    total += bytes;
+    return 0;
+}
+
+int upload_list_ptr_table(ivf_index* x) {
+    HIP_TRY(hipMemcpy(x->d_list_ptr, x->dev_ptr.data(), sizeof(void*) * (size_t)x->nlist,
+                      hipMemcpyHostToDevice));
+    return 0;
+}
+
+// Upper bound on score blocks (and scan items) of a batch: every query probing the
+// nprobe longest lists.
+int64_t block_bound(const ivf_index* x, int64_t nq, int nprobe) {
+    size_t p = std::min<size_t>((size_t)nprobe, x->top_nblk_prefix.size() - 1);
+    return nq * x->top_nblk_prefix[p];
+}
+
+int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
+    Scratch& s = x->sc;
+    const int64_t ntile = (x->nlist + kCoarseTile - 1) / kCoarseTile;
+    const size_t npairs = (size_t)nq * nprobe;
+    const size_t nblocks = (size_t)std::max<int64_t>(1, block_bound(x, nq, nprobe));
+    int rc;
+    if ((size_t)nq * x->nlist > s.cap_q_nlist) {
+        if ((rc = dalloc(s.S, (size_t)nq * x->nlist, s.bytes))) return rc;
+        s.cap_q_nlist = (size_t)nq * x->nlist;
+    }
+    if ((size_t)nq * ntile > s.cap_q_ntile) {
+        if ((rc = dalloc(s.tmax, (size_t)nq * ntile, s.bytes))) return rc;
+        s.cap_q_ntile = (size_t)nq * ntile;
+    }
+    if (x->nlist > s.cap_nlist) {
+        if ((rc = dalloc(s.zeroed, 2 * (size_t)x->nlist + 16, s.bytes))) return rc;
+        if ((rc = dalloc(s.pair_start, (size_t)x->nlist, s.bytes))) return rc;
+        if ((rc = dalloc(s.sblk_start, (size_t)x->nlist, s.bytes))) return rc;
+        if ((rc = dalloc(s.item_start, (size_t)x->nlist, s.bytes))) return rc;
+        if ((rc = dalloc(s.counters, (size_t)kNumCounters, s.bytes))) return rc;
+        s.cap_nlist = x->nlist;
+        if (!s.h_counters)
+            HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&s.h_counters), sizeof(unsigned long long) * kNumCounters));
+    }
+    if (npairs > s.cap_pairs) {
+        if ((rc = dalloc(s.probes, npairs, s.bytes))) return rc;
+        if ((rc = dalloc(s.pair_flat, npairs, s.bytes))) return rc;
+        if ((rc = dalloc(s.pair_q, npairs, s.bytes))) return rc;
+        if ((rc = dalloc(s.pair_of_probe, npairs, s.bytes))) return rc;
+        s.cap_pairs = npairs;
+    }
+    if (nblocks > s.cap_blocks) {
+        if ((rc = dalloc(s.items, nblocks, s.bytes))) return rc;
+        if ((rc = dalloc(s.scores, nblocks * kLanes, s.bytes))) return rc;
+        if ((rc = dalloc(s.bmax, nblocks, s.bytes))) return rc;
+        s.cap_blocks = nblocks;
+    }
+    if (offload) {
+        if (nblocks > s.cap_stream_items) {
+            if ((rc = dalloc(s.stream_items, nblocks, s.bytes))) return rc;
+            s.cap_stream_items = nblocks;
+        }
+        if (npairs > s.h_probes_cap) {
+            if (s.h_probes) (void)hipHostFree(s.h_probes);
+            s.h_probes = nullptr;
+            if (hipHostMalloc(reinterpret_cast<void**>(&s.h_probes), npairs * sizeof(int32_t)) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(IVF_ERR_OOM_HOST, "pinned allocation of the probe mirror failed");
+            }
+            s.h_probes_cap = npairs;
+        }
+        if (nblocks > s.h_items_cap) {
+            if (s.h_items) (void)hipHostFree(s.h_items);
+            s.h_items = nullptr;
+            if (hipHostMalloc(reinterpret_cast<void**>(&s.h_items), nblocks * sizeof(ScanItem)) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(IVF_ERR_OOM_HOST, "pinned allocation of the item mirror failed");
+            }
+            s.h_items_cap = nblocks;
+        }
+    }
+    return 0;
+}
+
+template <bool HALF>
+void launch_scan_u(ivf_index* x, int U, dim3 grid, hipStream_t st, const ScanItem* items,
+                   const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
+    Scratch& s = x->sc;
+    unsigned int* queue = reinterpret_cast<unsigned int*>(s.zeroed + 2 * (size_t)x->nlist);
+    switch (U) {
+        case 4:
+            hipLaunchKernelGGL((k_scan<HALF, 4>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
+                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
+            break;
+        case 16:
+            hipLaunchKernelGGL((k_scan<HALF, 16>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
+                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
+            break;
+        default:
+            hipLaunchKernelGGL((k_scan<HALF, 8>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
+                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
+    }
+}
+
+void launch_scan(ivf_index* x, dim3 grid, hipStream_t st, const ScanItem* items,
+                 const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
+    if (x->dtype == IVF_FP16)
+        launch_scan_u<true>(x, (int)x->opt_scan_unroll, grid, st, items, n_dev, n_host, Q, mode);
+    else
+        launch_scan_u<false>(x, (int)x->opt_scan_unroll, grid, st, items, n_dev, n_host, Q, mode);
+}
+
+int ensure_staging(ivf_index* x) {
+    size_t max_list_bytes = 0;
+    for (int64_t l = 0; l < x->nlist; ++l)
+        max_list_bytes = std::max(max_list_bytes, (size_t)x->nblk[l] * x->block_bytes);
+    size_t want = std::max<size_t>((size_t)x->opt_stage_mb << 20, max_list_bytes);
+    int nst = (int)std::min<int64_t>(kMaxStage, std::max<int64_t>(2, x->opt_nstage));
+    if (x->nstage == nst && x->stage_bytes >= want) return 0;
+    free_staging(x);
+    for (int i = 0; i < nst; ++i) {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&x->stage[i]), want);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            free_staging(x);
+            return fail(IVF_ERR_OOM_DEVICE, "staging buffer of %zu bytes: %s", want, hipGetErrorString(e));
+        }
+    }
+    x->nstage = nst;
+    x->stage_bytes = want;
+    return 0;
+}
+
+// The host-resident part of a search: mirror the device's pair numbering, pack the
+// probed host lists into staging-sized chunks, copy each chunk on the side stream and
+// scan it on the caller's stream as soon as it has landed.
+int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipStream_t st) {
+    Scratch& s = x->sc;
+    HIP_TRY(hipEventSynchronize(x->ev_probes));
+    HIP_TRY(hipStreamSynchronize(x->side));   // pinned item mirror of the previous search is free
+    const size_t npairs = (size_t)nq * nprobe;
+    std::vector<std::pair<int32_t, uint32_t>> pl(npairs);
+    for (size_t f = 0; f < npairs; ++f) pl[f] = {s.h_probes[f], (uint32_t)f};
+    std::sort(pl.begin(), pl.end());
+    ivf_search_stats& stt = x->last_stats;
+    stt = ivf_search_stats();
+    stt.pairs = (int64_t)npairs;
+
+    struct HostList { int32_t l; uint32_t cnt, ps, sb; };
+    std::vector<HostList> hl;
+    uint32_t ps = 0, sb = 0;
+    for (size_t i = 0; i < npairs;) {
+        size_t j = i;
+        while (j < npairs && pl[j].first == pl[i].first) ++j;
+        int32_t l = pl[i].first;
+        uint32_t cnt = (uint32_t)(j - i);
+        stt.unique_lists += 1;
+        stt.scanned_vectors += x->len[l];
+        int64_t bytes = (int64_t)x->len[l] * (int64_t)x->row_bytes;
+        stt.scan_bytes += bytes;
+        if (x->dev_ptr[l]) {
+            stt.scan_bytes_resident += bytes;
+            stt.scan_items += (int64_t)x->nblk[l] * ((cnt + kQB - 1) / kQB);
+        } else {
+            stt.scan_bytes_streamed += bytes;
+            if (x->nblk[l] > 0) hl.push_back({l, cnt, ps, sb});
+        }
+        ps += cnt;
+        sb += cnt * (uint32_t)x->nblk[l];
+        i = j;
+    }
+    if (x->done_recorded) HIP_TRY(hipStreamWaitEvent(x->side, x->ev_done, 0));
+
+    size_t item_off = 0;
+    size_t i = 0;
+    int chunk = 0;
+    while (i < hl.size()) {
+        const int slot = chunk % x->nstage;
+        size_t used = 0, j = i;
+        while (j < hl.size()) {
+            size_t b = (size_t)x->nblk[hl[j].l] * x->block_bytes;
+            if (used + b > x->stage_bytes) break;
+            used += b;
+            ++j;
+        }
+        if (j == i) return fail(IVF_ERR_LIMIT, "staging buffer smaller than a list");
+        if (x->stage_used[slot]) HIP_TRY(hipStreamWaitEvent(x->side, x->stage_free[slot], 0));
+        // copies: merge lists that are neighbours in the host arena
+        size_t dst_off = 0;
+        size_t a = i;
+        const size_t item_begin = item_off;
+        while (a < j) {
+            const char* src = x->host_ptr[hl[a].l];
+            size_t bytes = (size_t)x->nblk[hl[a].l] * x->block_bytes;
+            size_t e = a + 1;
+            while (e < j && x->host_ptr[hl[e].l] == src + bytes) {
+                bytes += (size_t)x->nblk[hl[e].l] * x->block_bytes;
+                ++e;
+            }
+            HIP_TRY(hipMemcpyAsync(x->stage[slot] + dst_off, src, bytes, hipMemcpyHostToDevice, x->side));
+            dst_off += bytes;
+            a = e;
+        }
+        // items of the chunk
+        size_t loff = 0;
+        for (size_t t = i; t < j; ++t) {
+            const HostList& h = hl[t];
+            const uint32_t nb = (uint32_t)x->nblk[h.l];
+            const uint32_t groups = (h.cnt + kQB - 1) / kQB;
+            for (uint32_t g = 0; g < groups; ++g)
+                for (uint32_t b = 0; b < nb; ++b) {
+                    ScanItem it;
+                    it.data = x->stage[slot] + loff + (size_t)b * x->block_bytes;
+                    it.sblk = h.sb + g * kQB * nb + b;
+                    it.nblk = nb;
+                    it.pair0 = h.ps + g * kQB;
+                    it.nq = std::min<uint32_t>(kQB, h.cnt - g * kQB);
+                    it.nvalid = std::min<uint32_t>(64u, (uint32_t)x->len[h.l] - b * 64u);
+                    it.pad = 0;
+                    s.h_items[item_off++] = it;
+                }
+            loff += (size_t)nb * x->block_bytes;
+        }
+        const size_t nitems = item_off - item_begin;
+        HIP_TRY(hipMemcpyAsync(s.stream_items + item_begin, s.h_items + item_begin,
+                               nitems * sizeof(ScanItem), hipMemcpyHostToDevice, x->side));
+        HIP_TRY(hipEventRecord(x->stage_ready[slot], x->side));
+        HIP_TRY(hipStreamWaitEvent(st, x->stage_ready[slot], 0));
+        dim3 grid((unsigned)((nitems + kScanWaves - 1) / kScanWaves));
+        launch_scan(x, grid, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q, 0);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(x->stage_free[slot], st));
+        x->stage_used[slot] = true;
+        stt.scan_items += (int64_t)nitems;
+        i = j;
+        ++chunk;
+    }
+    return 0;
+}
+
+int check_ready(const ivf_index* x) {
+    if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
+    if (!x->ready) return fail(IVF_ERR_INVALID, "index has no uploaded data");
+    return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ivf_last_error(void) { return g_err.c_str(); }
+
+int ivf_index_create(ivf_index** out) {
+    if (!out) return fail(IVF_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    ivf_index* x = new (std::nothrow) ivf_index();
+    if (!x) return fail(IVF_ERR_OOM_HOST, "out of host memory");
+    hipError_t e = hipGetDevice(&x->device);
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, x->device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_probes, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_done, hipEventDisableTiming);
+    for (int i = 0; e == hipSuccess && i < kMaxStage; ++i) {
+        e = hipEventCreateWithFlags(&x->stage_ready[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&x->stage_free[i], hipEventDisableTiming);
+    }
+    for (int i = 0; e == hipSuccess && i <= IVF_NUM_STAGES; ++i) e = hipEventCreate(&x->ev[i]);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        int rc = fail(IVF_ERR_HIP, "index creation failed: %s", hipGetErrorString(e));
+        ivf_index_destroy(x);
+        return rc;
+    }
+    x->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    *out = x;
+    return 0;
+}
+
+void ivf_index_destroy(ivf_index* x) {
+    if (!x) return;
+    (void)hipDeviceSynchronize();
+    free_index_data(x);
+    if (x->side) (void)hipStreamDestroy(x->side);
+    if (x->ev_probes) (void)hipEventDestroy(x->ev_probes);
+    if (x->ev_done) (void)hipEventDestroy(x->ev_done);
+    for (int i = 0; i < kMaxStage; ++i) {
+        if (x->stage_ready[i]) (void)hipEventDestroy(x->stage_ready[i]);
+        if (x->stage_free[i]) (void)hipEventDestroy(x->stage_free[i]);
+    }
+    for (int i = 0; i <= IVF_NUM_STAGES; ++i)
+        if (x->ev[i]) (void)hipEventDestroy(x->ev[i]);
+    delete x;
+}
+
+int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const float* centroids,
+                           int dtype, const int64_t* list_offsets) {
+    if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
+    if (!centroids || !list_offsets) return fail(IVF_ERR_INVALID, "centroids or list_offsets is NULL");
+    if (dtype != IVF_FP32 && dtype != IVF_FP16) return fail(IVF_ERR_INVALID, "dtype must be IVF_FP32 or IVF_FP16");
+    if (d <= 0 || nlist <= 0 || n < 0) return fail(IVF_ERR_INVALID, "d, nlist must be positive and n non-negative");
+    if (d % 8 != 0 || d > 4096) return fail(IVF_ERR_LIMIT, "d must be a multiple of 8 and at most 4096 (got %d)", d);
+    if (n >= (int64_t)1 << 32 || nlist >= (int64_t)1 << 31)
+        return fail(IVF_ERR_LIMIT, "n must be below 2^32 and nlist below 2^31");
+    (void)hipDeviceSynchronize();
+    free_index_data(x);
+    x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : 4;
+    x->nlist = nlist; x->n = n;
+    x->row_bytes = (size_t)d * x->es;
+    x->block_bytes = x->row_bytes * kLanes;
+    try {
+        x->offsets.assign((size_t)nlist + 1, 0);
+        x->blk_off.assign((size_t)nlist + 1, 0);
+        x->len.assign((size_t)nlist, 0);
+        x->nblk.assign((size_t)nlist, 0);
+        x->dev_ptr.assign((size_t)nlist, nullptr);
+        x->host_ptr.assign((size_t)nlist, nullptr);
+    } catch (const std::bad_alloc&) {
+        return fail(IVF_ERR_OOM_HOST, "out of host memory for the list tables");
+    }
+    HIP_TRY(hipMemcpy(x->offsets.data(), list_offsets, sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyDefault));
+    if (x->offsets[0] != 0 || x->offsets[(size_t)nlist] != n)
+        return fail(IVF_ERR_INVALID, "list_offsets must start at 0 and end at n");
+    x->max_len = 0;
+    for (int64_t l = 0; l < nlist; ++l) {
+        int64_t ln = x->offsets[l + 1] - x->offsets[l];
+        if (ln < 0) return fail(IVF_ERR_INVALID, "list_offsets must be non-decreasing (list %lld)", (long long)l);
+        if (ln > (int64_t)65535 * kLanes) return fail(IVF_ERR_LIMIT, "list %lld longer than %d vectors", (long long)l, 65535 * kLanes);
+        x->len[l] = (int32_t)ln;
+        x->nblk[l] = (int32_t)((ln + kLanes - 1) / kLanes);
+        x->blk_off[l + 1] = x->blk_off[l] + x->nblk[l];
+        x->max_len = std::max(x->max_len, ln);
+    }
+    x->total_blocks = x->blk_off[(size_t)nlist];
+    {
+        std::vector<int32_t> srt(x->nblk);
+        std::sort(srt.begin(), srt.end(), std::greater<int32_t>());
+        size_t m = std::min<size_t>(srt.size(), kMaxK);
+        x->top_nblk_prefix.assign(m + 1, 0);
+        for (size_t i = 0; i < m; ++i) x->top_nblk_prefix[i + 1] = x->top_nblk_prefix[i] + srt[i];
+    }
+    size_t tot = 0;
+    int rc;
+    if ((rc = dalloc(x->d_centroids, (size_t)nlist * d, tot))) return rc;
+    if ((rc = dalloc(x->d_offsets, (size_t)nlist + 1, tot))) return rc;
+    if ((rc = dalloc(x->d_blk_off, (size_t)nlist + 1, tot))) return rc;
+    if ((rc = dalloc(x->d_len, (size_t)nlist, tot))) return rc;
+    if ((rc = dalloc(x->d_nblk, (size_t)nlist, tot))) return rc;
+    if ((rc = dalloc(x->d_list_ptr, (size_t)nlist, tot))) return rc;
+    if ((rc = dalloc(x->d_ids_pos, (size_t)n, tot))) return rc;
+    x->d_arena_bytes = std::max<size_t>((size_t)x->total_blocks * x->block_bytes, 256);
+    {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&x->d_arena), x->d_arena_bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            x->d_arena = nullptr;
+            return fail(IVF_ERR_OOM_DEVICE, "list arena of %zu bytes: %s", x->d_arena_bytes, hipGetErrorString(e));
+        }
+    }
+    HIP_TRY(hipMemcpy(x->d_centroids, centroids, sizeof(float) * (size_t)nlist * d, hipMemcpyDefault));
+    HIP_TRY(hipMemcpy(x->d_offsets, x->offsets.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(x->d_blk_off, x->blk_off.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(x->d_len, x->len.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(x->d_nblk, x->nblk.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
+    for (int64_t l = 0; l < nlist; ++l) x->dev_ptr[l] = x->d_arena + (size_t)x->blk_off[l] * x->block_bytes;
+    x->resident_lists = nlist;
+    x->next_list = 0;
+    x->uploading = true;
+    return 0;
+}
+
+int ivf_index_upload_lists(ivf_index* x, int64_t list_begin, int64_t list_end, const void* vectors,
+                           const int64_t* ids) {
+    if (!x || !x->uploading) return fail(IVF_ERR_INVALID, "upload_lists without upload_begin");
+    if (list_begin != x->next_list || list_end < list_begin || list_end > x->nlist)
+        return fail(IVF_ERR_INVALID, "pieces must cover the lists in ascending order without gaps (expected list %lld)",
+                    (long long)x->next_list);
+    const int64_t r0 = x->offsets[list_begin], r1 = x->offsets[list_end];
+    const int64_t rows = r1 - r0;
+    if (rows > 0 && (!vectors || !ids)) return fail(IVF_ERR_INVALID, "vectors or ids is NULL");
+    if (rows > 0) {
+        HIP_TRY(hipMemcpy(x->d_ids_pos + r0, ids, sizeof(int64_t) * (size_t)rows, hipMemcpyDefault));
+        const bool on_dev = is_device_ptr(vectors);
+        char* tmp = nullptr;
+        size_t tmp_bytes = 0;
+        if (!on_dev) {
+            tmp_bytes = std::max<size_t>((size_t)256 << 20, (size_t)x->max_len * x->row_bytes);
+            tmp_bytes = std::min(tmp_bytes, (size_t)rows * x->row_bytes);
+            hipError_t e = hipMalloc(reinterpret_cast<void**>(&tmp), tmp_bytes);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(IVF_ERR_OOM_DEVICE, "upload staging of %zu bytes: %s", tmp_bytes, hipGetErrorString(e));
+            }
+        }
+        int64_t lb = list_begin;
+        int rc = 0;
+        while (lb < list_end && rc == 0) {
+            int64_t le = lb;
+            if (on_dev) {
+                le = list_end;
+            } else {
+                while (le < list_end && (size_t)(x->offsets[le + 1] - x->offsets[lb]) * x->row_bytes <= tmp_bytes) ++le;
+            }
+            const int64_t pr = x->offsets[le] - x->offsets[lb];
+            int32_t maxnb = 0;
+            for (int64_t l = lb; l < le; ++l) maxnb = std::max(maxnb, x->nblk[l]);
+            if (pr > 0) {
+                const char* src = static_cast<const char*>(vectors) + (size_t)(x->offsets[lb] - r0) * x->row_bytes;
+                hipError_t e = hipSuccess;
+                if (!on_dev) {
+                    e = hipMemcpy(tmp, src, (size_t)pr * x->row_bytes, hipMemcpyHostToDevice);
+                    src = tmp;
+                }
+                if (e == hipSuccess) {
+                    dim3 grid((unsigned)(le - lb), (unsigned)maxnb);
+                    hipLaunchKernelGGL(k_relayout, grid, dim3(256), 0, 0, src, x->d_offsets, x->d_blk_off, lb,
+                                       (int)x->row_bytes, x->d_arena);
+                    e = hipGetLastError();
+                    if (e == hipSuccess) e = hipDeviceSynchronize();
+                }
+                if (e != hipSuccess) {
+                    (void)hipGetLastError();
+                    rc = fail(IVF_ERR_HIP, "re-layout of lists [%lld,%lld) failed: %s", (long long)lb, (long long)le,
+                              hipGetErrorString(e));
+                }
+            }
+            lb = le;
+        }
+        if (tmp) (void)hipFree(tmp);
+        if (rc) return rc;
+    }
+    x->next_list = list_end;
+    return 0;
+}
+
+int ivf_index_upload_end(ivf_index* x) {
+    if (!x || !x->uploading) return fail(IVF_ERR_INVALID, "upload_end without upload_begin");
+    if (x->next_list != x->nlist)
+        return fail(IVF_ERR_INVALID, "only %lld of %lld lists were uploaded", (long long)x->next_list, (long long)x->nlist);
+    size_t tot = 0;
+    int rc;
+    const size_t n = (size_t)x->n;
+    uint32_t* pos_in = nullptr;
+    uint32_t* pos_sorted = nullptr;
+    if ((rc = dalloc(x->d_id_sorted, n, tot))) return rc;
+    if ((rc = dalloc(x->d_rank_of_pos, n, tot))) return rc;
+    if ((rc = dalloc(pos_in, n, tot))) return rc;
+    if ((rc = dalloc(pos_sorted, n, tot))) { dfree(pos_in); return rc; }
+    if (n > 0) {
+        const unsigned g = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_iota_u32, dim3(g), dim3(256), 0, 0, pos_in, n);
+        int e = ivf_internal_sort_pairs(x->d_ids_pos, x->d_id_sorted, pos_in, pos_sorted, n, 0);
+        if (e == 0) {
+            hipLaunchKernelGGL(k_scatter_rank, dim3(g), dim3(256), 0, 0, pos_sorted, x->d_rank_of_pos, n);
+            e = (int)hipDeviceSynchronize();
+        }
+        if (e != 0) {
+            (void)hipGetLastError();
+            dfree(pos_in); dfree(pos_sorted);
+            return fail(e == (int)hipErrorOutOfMemory ? IVF_ERR_OOM_DEVICE : IVF_ERR_HIP, "id ranking failed: %s",
+                        hipGetErrorString((hipError_t)e));
+        }
+    }
+    dfree(pos_in);
+    dfree(pos_sorted);
+    dfree(x->d_ids_pos);
+    if ((rc = upload_list_ptr_table(x))) return rc;
+    x->uploading = false;
+    x->ready = true;
+    return 0;
+}
+
+int ivf_index_upload(ivf_index* x, int d, int64_t nlist, int64_t n, const float* centroids,
+                     const void* vectors, int dtype, const int64_t* ids, const int64_t* list_offsets) {
+    int rc = ivf_index_upload_begin(x, d, nlist, n, centroids, dtype, list_offsets);
+    if (rc) return rc;
+    if ((rc = ivf_index_upload_lists(x, 0, nlist, vectors, ids))) return rc;
+    return ivf_index_upload_end(x);
+}
+
+int ivf_set_device_budget(ivf_index* x, int64_t bytes) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (bytes < 0) return fail(IVF_ERR_INVALID, "budget must be non-negative");
+    HIP_TRY(hipDeviceSynchronize());
+    const int64_t nlist = x->nlist;
+    std::vector<int32_t> order((size_t)nlist);
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (x->len[a] != x->len[b]) return x->len[a] > x->len[b];
+        return a < b;
+    });
+    std::vector<char> res((size_t)nlist, 0);
+    uint64_t used = 0;
+    int64_t nres = 0;
+    for (int32_t l : order) {
+        uint64_t b = (uint64_t)x->nblk[l] * x->block_bytes;
+        if (used + b > (uint64_t)bytes) break;
+        used += b;
+        res[l] = 1;
+        ++nres;
+    }
+    bool same = true;
+    for (int64_t l = 0; l < nlist && same; ++l) same = (res[l] != 0) == (x->dev_ptr[l] != nullptr);
+    if (same) return 0;
+    const size_t total = (size_t)x->total_blocks * x->block_bytes;
+    const size_t new_dev = (size_t)used, new_host = total - new_dev;
+    char* nd = nullptr;
+    char* nh = nullptr;
+    if (new_dev) {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&nd), new_dev);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(IVF_ERR_OOM_DEVICE, "new device arena of %zu bytes: %s", new_dev, hipGetErrorString(e));
+        }
+    }
+    if (new_host) {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&nh), new_host);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            if (nd) (void)hipFree(nd);
+            return fail(IVF_ERR_OOM_HOST, "pinned host arena of %zu bytes: %s", new_host, hipGetErrorString(e));
+        }
+    }
+    std::vector<const char*> ndp((size_t)nlist, nullptr), nhp((size_t)nlist, nullptr);
+    size_t doff = 0, hoff = 0;
+    hipError_t e = hipSuccess;
+    // copy runs of lists whose source and destination are both contiguous
+    const char* run_src = nullptr;
+    char* run_dst = nullptr;
+    size_t run_bytes = 0;
+    auto flush = [&]() {
+        if (run_bytes && e == hipSuccess) e = hipMemcpyAsync(run_dst, run_src, run_bytes, hipMemcpyDefault, 0);
+        run_bytes = 0;
+    };
+    for (int64_t l = 0; l < nlist; ++l) {
+        size_t b = (size_t)x->nblk[l] * x->block_bytes;
+        const char* src = x->dev_ptr[l] ? x->dev_ptr[l] : x->host_ptr[l];
+        char* dst;
+        if (res[l]) { dst = nd + doff; ndp[l] = dst; doff += b; }
+        else { dst = nh + hoff; nhp[l] = dst; hoff += b; }
+        if (!b) continue;
+        if (run_bytes && src == run_src + run_bytes && dst == run_dst + run_bytes) {
+            run_bytes += b;
+        } else {
+            flush();
+            run_src = src; run_dst = dst; run_bytes = b;
+        }
+    }
+    flush();
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (nd) (void)hipFree(nd);
+        if (nh) (void)hipHostFree(nh);
+        return fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(e));
+    }
+    // empty lists keep a non-null device address so that they count as resident
+    for (int64_t l = 0; l < nlist; ++l)
+        if (res[l] && !ndp[l]) ndp[l] = nd ? nd : reinterpret_cast<const char*>(x->d_centroids);
+    dfree(x->d_arena);
+    if (x->h_arena) (void)hipHostFree(x->h_arena);
+    x->d_arena = nd; x->d_arena_bytes = new_dev;
+    x->h_arena = nh; x->h_arena_bytes = new_host;
+    x->dev_ptr.swap(ndp);
+    x->host_ptr.swap(nhp);
+    x->resident_lists = nres;
+    if ((rc = upload_list_ptr_table(x))) return rc;
+    if (nres < nlist) {
+        if ((rc = ensure_staging(x))) return rc;
+    } else {
+        free_staging(x);
+    }
+    return 0;
+}
+
+int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
+               float* out_scores, void* stream) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (nq < 0) return fail(IVF_ERR_INVALID, "nq must be non-negative");
+    if (nq == 0) return 0;
+    if (!queries || !out_ids || !out_scores) return fail(IVF_ERR_INVALID, "queries, out_ids or out_scores is NULL");
+    if (nprobe <= 0 || k <= 0) return fail(IVF_ERR_INVALID, "nprobe and k must be positive");
+    if (k > kMaxK) return fail(IVF_ERR_LIMIT, "k above %d", kMaxK);
+    if (nprobe > x->nlist) nprobe = (int)x->nlist;
+    if (nprobe > kMaxK) return fail(IVF_ERR_LIMIT, "nprobe above %d", kMaxK);
+    if (nq > 65535) return fail(IVF_ERR_LIMIT, "nq above 65535");
+    if ((uint64_t)nq * (uint64_t)nprobe >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "nq*nprobe above 2^31");
+    if ((uint64_t)block_bound(x, nq, nprobe) >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "batch too large for one call");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool offload = x->resident_lists < x->nlist;
+    if (offload && (rc = ensure_staging(x))) return rc;
+    if ((rc = ensure_scratch(x, nq, nprobe, offload))) return rc;
+    Scratch& s = x->sc;
+    const int nlist = (int)x->nlist;
+    const int ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
+    const int npairs = (int)(nq * nprobe);
+    const bool tm = x->timing;
+    int evi = 0;
+    auto mark = [&]() { if (tm) (void)hipEventRecord(x->ev[evi], st); ++evi; };
+
+    mark();   // 0
+    {
+        size_t nz = 2 * (size_t)nlist + 16;
+        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, s.zeroed, nz);
+    }
+    {
+        dim3 grid((unsigned)((nlist + kCoarseNT - 1) / kCoarseNT), 1);
+        if (nq <= 32) {
+            grid.y = 1;
+            hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+        } else if (nq <= 64) {
+            grid.y = 1;
+            hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+        } else {
+            grid.y = (unsigned)((nq + 127) / 128);
+            hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+        }
+    }
+    mark();   // 1
+    int* hist = s.zeroed;
+    int* cursor = s.zeroed + nlist;
+    hipLaunchKernelGGL(k_probe_select, dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.S, s.tmax, nlist, ntile, nprobe,
+                       s.probes, hist);
+    mark();   // 2
+    if (offload) {
+        HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)npairs, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipEventRecord(x->ev_probes, st));
+    }
+    hipLaunchKernelGGL(k_list_scan, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr, nlist,
+                       s.pair_start, s.sblk_start, s.item_start, s.counters);
+    hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
+                       s.pair_start, cursor, s.pair_flat);
+    hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
+                       x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
+                       s.pair_flat, s.pair_q, s.pair_of_probe, s.items);
+    mark();   // 3
+    if (x->resident_lists > 0) {
+        const int mode = (int)x->opt_scan_mode;
+        dim3 grid;
+        if (mode == 0) {
+            int64_t bound = std::max<int64_t>(1, block_bound(x, nq, nprobe));
+            grid = dim3((unsigned)((bound + kScanWaves - 1) / kScanWaves));
+        } else {
+            grid = dim3((unsigned)(x->cus * std::max<int64_t>(1, x->opt_scan_wgs_per_cu)));
+        }
+        launch_scan(x, grid, st, s.items, s.counters + kCntItems, 0, queries, mode);
+    }
+    mark();   // 4
+    HIP_TRY(hipGetLastError());
+    if (offload) {
+        if ((rc = stream_host_lists(x, queries, nq, nprobe, st))) return rc;
+    }
+    mark();   // 5
+    ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
+    hipLaunchKernelGGL(k_final_select, dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.probes, s.pair_of_probe,
+                       s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, nprobe, k,
+                       out_ids, out_scores);
+    mark();   // 6
+    HIP_TRY(hipGetLastError());
+    if (offload) {
+        HIP_TRY(hipEventRecord(x->ev_done, st));
+        x->done_recorded = true;
+    }
+    x->last_nq = (int)nq;
+    x->last_nprobe = nprobe;
+    x->last_stream = st;
+    x->last_offload = offload;
+    x->ev_valid = tm;
+    return 0;
+}
+
+int ivf_get_info(ivf_index* x, ivf_info* out) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (!out) return fail(IVF_ERR_INVALID, "out is NULL");
+    out->d = x->d; out->dtype = x->dtype; out->nlist = x->nlist; out->n = x->n;
+    out->max_list_len = x->max_len;
+    out->index_bytes = (int64_t)((size_t)x->total_blocks * x->block_bytes);
+    int64_t dev = 0;
+    for (int64_t l = 0; l < x->nlist; ++l)
+        if (x->dev_ptr[l]) dev += (int64_t)x->nblk[l] * (int64_t)x->block_bytes;
+    out->device_list_bytes = dev;
+    out->host_list_bytes = out->index_bytes - dev;
+    out->resident_lists = x->resident_lists;
+    out->scratch_bytes = (int64_t)x->sc.bytes;
+    return 0;
+}
+
+int ivf_debug_last_probes(ivf_index* x, int32_t* out_lists, void* stream) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (!out_lists || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out_lists is NULL");
+    HIP_TRY(hipMemcpyAsync(out_lists, x->sc.probes, sizeof(int32_t) * (size_t)x->last_nq * x->last_nprobe,
+                           hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return 0;
+}
+
+int ivf_debug_last_coarse(ivf_index* x, float* out_scores, void* stream) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (!out_scores || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out_scores is NULL");
+    HIP_TRY(hipMemcpyAsync(out_scores, x->sc.S, sizeof(float) * (size_t)x->last_nq * (size_t)x->nlist,
+                           hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    return 0;
+}
+
+int ivf_debug_read_list(ivf_index* x, int64_t list, void* out_vectors, int64_t* out_ids, int64_t* len) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (list < 0 || list >= x->nlist) return fail(IVF_ERR_INVALID, "list out of range");
+    HIP_TRY(hipDeviceSynchronize());
+    const int64_t ln = x->len[list];
+    if (len) *len = ln;
+    if (ln == 0) return 0;
+    const size_t bytes = (size_t)x->nblk[list] * x->block_bytes;
+    if (out_vectors) {
+        char* blk = nullptr;
+        char* rows = nullptr;
+        const char* src = x->dev_ptr[list];
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&rows), (size_t)ln * x->row_bytes);
+        if (e == hipSuccess && !src) {
+            e = hipMalloc(reinterpret_cast<void**>(&blk), bytes);
+            if (e == hipSuccess) e = hipMemcpy(blk, x->host_ptr[list], bytes, hipMemcpyHostToDevice);
+            src = blk;
+        }
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_unlayout, dim3((unsigned)x->nblk[list]), dim3(256), 0, 0, src, ln, (int)x->row_bytes, rows);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpy(out_vectors, rows, (size_t)ln * x->row_bytes, hipMemcpyDeviceToHost);
+        if (rows) (void)hipFree(rows);
+        if (blk) (void)hipFree(blk);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(IVF_ERR_HIP, "read-back failed: %s", hipGetErrorString(e));
+        }
+    }
+    if (out_ids) {
+        int64_t* tmp = nullptr;
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&tmp), sizeof(int64_t) * (size_t)ln);
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(k_gather_ids, dim3((unsigned)((ln + 255) / 256)), dim3(256), 0, 0, x->d_id_sorted,
+                               x->d_rank_of_pos, x->offsets[list], ln, tmp);
+            e = hipMemcpy(out_ids, tmp, sizeof(int64_t) * (size_t)ln, hipMemcpyDeviceToHost);
+        }
+        if (tmp) (void)hipFree(tmp);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(IVF_ERR_HIP, "id read-back failed: %s", hipGetErrorString(e));
+        }
+    }
+    return 0;
+}
+
+int ivf_last_search_stats(ivf_index* x, ivf_search_stats* out) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (!out || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out is NULL");
+    HIP_TRY(hipStreamSynchronize(x->last_stream));
+    if (!x->last_offload) {
+        Scratch& s = x->sc;
+        HIP_TRY(hipMemcpy(s.h_counters, s.counters, sizeof(unsigned long long) * kNumCounters, hipMemcpyDeviceToHost));
+        ivf_search_stats t = {};
+        t.pairs = (int64_t)s.h_counters[kCntPairs];
+        t.unique_lists = (int64_t)s.h_counters[kCntUnique];
+        t.scanned_vectors = (int64_t)s.h_counters[kCntVectors];
+        t.scan_bytes = t.scanned_vectors * (int64_t)x->row_bytes;
+        t.scan_bytes_resident = (int64_t)s.h_counters[kCntVectorsResident] * (int64_t)x->row_bytes;
+        t.scan_bytes_streamed = t.scan_bytes - t.scan_bytes_resident;
+        t.scan_items = (int64_t)s.h_counters[kCntItems];
+        x->last_stats = t;
+    }
+    *out = x->last_stats;
+    return 0;
+}
+
+int ivf_set_timing(ivf_index* x, int enable) {
+    if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
+    x->timing = enable != 0;
+    x->ev_valid = false;
+    return 0;
+}
+
+int ivf_get_stage_ms(ivf_index* x, float* ms) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (!ms) return fail(IVF_ERR_INVALID, "ms is NULL");
+    if (!x->ev_valid) return fail(IVF_ERR_INVALID, "timing was not enabled for the last search");
+    HIP_TRY(hipEventSynchronize(x->ev[6]));
+    for (int i = 0; i < 6; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], x->ev[i], x->ev[i + 1]));
+    HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_TOTAL], x->ev[0], x->ev[6]));
+    return 0;
+}
+
+int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
+    if (!x || !name) return fail(IVF_ERR_INVALID, "index or name is NULL");
+    std::string n(name);
+    if (n == "scan_mode" && (value == 0 || value == 1)) x->opt_scan_mode = value;
+    else if (n == "scan_unroll" && (value == 4 || value == 8 || value == 16)) x->opt_scan_unroll = value;
+    else if (n == "scan_wgs_per_cu" && value >= 1 && value <= 16) x->opt_scan_wgs_per_cu = value;
+    else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
+    else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
+    else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);
+    return 0;
+}
+
+}  // extern "C"

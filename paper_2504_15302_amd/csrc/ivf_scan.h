@@ -1,0 +1,270 @@
+// The list scan: inner products of every vector of every probed list with every query
+// that probes the list.  HBM-bound (about one multiply-add per byte loaded), so the
+// kernel is built around the loads:
+//   * storage is blocked as [block of 64 vectors][d/E chunks][64 lanes][16 bytes]
+//     (E = 8 for fp16, 4 for fp32): a lane owns one vector, every load instruction of
+//     a wavefront fetches one contiguous 1 KiB line, and no cross-lane reduction is
+//     needed for the dot product;
+//   * a wavefront streams one block (64*d*elem bytes, contiguous) with two register
+//     buffers of U loads each, so loads of the next chunk group are in flight while
+//     the current one is multiplied;
+//   * the query values are wave-uniform: a lane loads one query value per dimension of
+//     the group (one coalesced load per query and group, served by L2), and each value
+//     is broadcast with a lane read and enters the FMA as a scalar operand — no LDS,
+//     no dependence on d, one vector register per query and 64 dimensions;
+//   * up to kQB queries that probe the same list share one read of the block;
+//   * scores go to a scratch array (4 bytes per vector and query, ~0.3 % of the bytes
+//     read) together with the maximum of each block of 64, which the final selection
+//     uses to visit only the few blocks that can hold a top-k member.
+#pragma once
+#include "ivf_device.h"
+
+namespace ivf {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef const u4 __attribute__((address_space(1))) * gptr_u4;   // global (HBM) address space
+
+// max over the 64 lanes through the LDS crossbar (no LDS memory is touched)
+__device__ __forceinline__ float wave_max(float v, int lane) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        int other = __builtin_amdgcn_ds_bpermute((lane ^ o) << 2, __float_as_int(v));
+        v = fmaxf(v, __int_as_float(other));
+    }
+    return v;
+}
+
+template <bool HALF> struct Store;
+template <> struct Store<true> { static constexpr int E = 8; };
+template <> struct Store<false> { static constexpr int E = 4; };
+
+// One group of UU consecutive 16-byte chunks of the lane's vector plus the matching
+// slice of each query, spread one value per lane (lane j holds dimension dim0 + j).
+template <int NQ, int UU, int E>
+struct ScanBuf {
+    static constexpr int G = UU * E;             // dimensions covered
+    static constexpr int QV = (G + 63) / 64;     // query registers per query
+    u4 x[UU];
+    float q[NQ][QV];
+};
+
+template <int NQ, int UU, int E>
+__device__ __forceinline__ void load_group(ScanBuf<NQ, UU, E>& b, gptr_u4 src, int chunk0,
+                                           const float* const (&qrow)[NQ], int lane) {
+    using B = ScanBuf<NQ, UU, E>;
+#pragma unroll
+    for (int u = 0; u < UU; ++u) b.x[u] = __builtin_nontemporal_load(src + (size_t)(chunk0 + u) * kLanes);
+    const int dim0 = chunk0 * E;
+#pragma unroll
+    for (int g = 0; g < NQ; ++g)
+#pragma unroll
+        for (int v = 0; v < B::QV; ++v) {
+            int j = v * 64 + lane;
+            if (B::G % 64 != 0) j = min(j, B::G - 1);     // idle lanes re-read the last value
+            b.q[g][v] = qrow[g][dim0 + j];
+        }
+}
+
+// acc[g] += sum over the group's dimensions of x * q[g]; the query value of a
+// dimension is broadcast from the lane that holds it and enters the FMA as a scalar.
+template <bool HALF, int NQ, int UU, int E>
+__device__ __forceinline__ void fma_group(const ScanBuf<NQ, UU, E>& b, float (&acc)[NQ]) {
+#pragma unroll
+    for (int u = 0; u < UU; ++u) {
+        float xf[E];
+        if constexpr (HALF) {
+            h8 x = __builtin_bit_cast(h8, b.x[u]);
+#pragma unroll
+            for (int h = 0; h < E; ++h) xf[h] = (float)x[h];
+        } else {
+            f4 x = __builtin_bit_cast(f4, b.x[u]);
+#pragma unroll
+            for (int h = 0; h < E; ++h) xf[h] = x[h];
+        }
+        // The empty asm makes the query register opaque here, so the lane reads of this
+        // chunk stay next to its FMAs; hoisted to the load they would need 64 scalar
+        // registers per query and spill.
+        float qreg[NQ];
+#pragma unroll
+        for (int g = 0; g < NQ; ++g) {
+            qreg[g] = b.q[g][(u * E) / 64];
+            asm volatile("" : "+v"(qreg[g]));
+        }
+        float qs[NQ][E];
+#pragma unroll
+        for (int h = 0; h < E; ++h)
+#pragma unroll
+            for (int g = 0; g < NQ; ++g)
+                qs[g][h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[g]), (u * E + h) % 64));
+#pragma unroll
+        for (int h = 0; h < E; ++h)
+#pragma unroll
+            for (int g = 0; g < NQ; ++g) acc[g] = __builtin_fmaf(xf[h], qs[g][h], acc[g]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <bool HALF, int NQ, int U>
+__device__ __forceinline__ void scan_item(const ScanItem& it, const float* __restrict__ Q,
+                                          const uint32_t* __restrict__ pair_q, int d,
+                                          float* __restrict__ scores, float* __restrict__ bmax,
+                                          int lane) {
+    constexpr int E = Store<HALF>::E;
+    const int nchunk = d / E;
+    const int nq = (int)it.nq;
+    // lanes past the end of the list re-read the last valid vector (same cache lines,
+    // no extra traffic, no divergence); their results are discarded below
+    const int ld_lane = min(lane, (int)it.nvalid - 1);
+    const gptr_u4 src = (gptr_u4)(uintptr_t)it.data + ld_lane;
+
+    const float* qrow[NQ];
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+        uint32_t qi = pair_q[it.pair0 + (uint32_t)min(g, nq - 1)];
+        qrow[g] = Q + (size_t)qi * d;
+    }
+    float acc[NQ];
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) acc[g] = 0.f;
+
+    // two register buffers: the loads of group i+1 are in flight while group i is used
+    ScanBuf<NQ, U, E> bufA, bufB;
+    const int ngroup = nchunk / U;
+    if (ngroup > 0) {
+        int gi = 0;
+        load_group(bufA, src, 0, qrow, lane);
+        for (; gi + 2 < ngroup; gi += 2) {           // bufA holds group gi
+            load_group(bufB, src, (gi + 1) * U, qrow, lane);
+            fma_group<HALF>(bufA, acc);
+            load_group(bufA, src, (gi + 2) * U, qrow, lane);
+            fma_group<HALF>(bufB, acc);
+        }
+        if (gi + 1 < ngroup) {
+            load_group(bufB, src, (gi + 1) * U, qrow, lane);
+            fma_group<HALF>(bufA, acc);
+            fma_group<HALF>(bufB, acc);
+        } else {
+            fma_group<HALF>(bufA, acc);
+        }
+    }
+    for (int c = ngroup * U; c < nchunk; ++c) {     // d not a multiple of the group width
+        ScanBuf<NQ, 1, E> one;
+        load_group(one, src, c, qrow, lane);
+        fma_group<HALF>(one, acc);
+    }
+
+    const bool valid = lane < (int)it.nvalid;
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+        if (g < nq) {
+            float s = valid ? acc[g] : -INFINITY;
+            uint32_t sb = it.sblk + (uint32_t)g * it.nblk;
+            scores[(size_t)sb * kLanes + lane] = s;
+            float mx = wave_max(s, lane);
+            if (lane == 0) bmax[sb] = mx;
+        }
+    }
+}
+
+template <bool HALF, int U>
+__device__ __forceinline__ void scan_dispatch(const ScanItem& it, const float* __restrict__ Q,
+                                              const uint32_t* __restrict__ pair_q, int d,
+                                              float* __restrict__ scores, float* __restrict__ bmax,
+                                              int lane) {
+    if (it.nq == 1)
+        scan_item<HALF, 1, U>(it, Q, pair_q, d, scores, bmax, lane);
+    else if (it.nq == 2)
+        scan_item<HALF, 2, U>(it, Q, pair_q, d, scores, bmax, lane);
+    else
+        scan_item<HALF, kQB, U>(it, Q, pair_q, d, scores, bmax, lane);
+}
+
+constexpr int kScanWaves = 4;   // wavefronts per workgroup of the scan
+
+// mode 0: one wavefront per item, grid sized by the host's upper bound on the items;
+// mode 1: persistent wavefronts pulling items from an atomic queue (*queue must be 0).
+// The item count comes from device memory (n_items_dev) when the plan was made on the
+// device, else from the host (n_items_host).
+template <bool HALF, int U>
+__global__ __launch_bounds__(kScanWaves * 64) void k_scan(
+    const ScanItem* __restrict__ items, const unsigned long long* __restrict__ n_items_dev,
+    uint32_t n_items_host, const float* __restrict__ Q, const uint32_t* __restrict__ pair_q, int d,
+    float* __restrict__ scores, float* __restrict__ bmax, int mode, unsigned int* __restrict__ queue) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t T = n_items_dev ? (uint32_t)*n_items_dev : n_items_host;
+    if (mode == 0) {
+        uint32_t t = blockIdx.x * kScanWaves + wave;
+        if (t >= T) return;
+        ScanItem it = items[t];
+        scan_dispatch<HALF, U>(it, Q, pair_q, d, scores, bmax, lane);
+    } else {
+        for (;;) {
+            uint32_t t = 0;
+            if (lane == 0) t = atomicAdd(queue, 1u);
+            t = __builtin_amdgcn_readfirstlane(t);
+            if (t >= T) break;           // every wavefront reaches this: the queue only grows
+            ScanItem it = items[t];
+            scan_dispatch<HALF, U>(it, Q, pair_q, d, scores, bmax, lane);
+        }
+    }
+}
+
+// Upload-time re-layout: row-major rows of a piece of the index -> blocked storage.
+// grid.x = list within the piece, grid.y = block within the list.
+__global__ __launch_bounds__(256) void k_relayout(const char* __restrict__ src_rows,
+                                                  const int64_t* __restrict__ offsets,
+                                                  const int64_t* __restrict__ blk_off,
+                                                  int64_t list_begin, int row_bytes,
+                                                  char* __restrict__ arena) {
+    const int64_t l = list_begin + blockIdx.x;
+    const int64_t len = offsets[l + 1] - offsets[l];
+    const int64_t b = blockIdx.y;
+    if (b * kLanes >= len) return;
+    const int64_t row0 = offsets[l] - offsets[list_begin] + b * kLanes;
+    const int nchunk = row_bytes / 16;
+    u4* dst = reinterpret_cast<u4*>(arena + (size_t)(blk_off[l] + b) * kLanes * (size_t)row_bytes);
+    for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
+        int c = u / kLanes, lane = u % kLanes;
+        u4 v = {0u, 0u, 0u, 0u};
+        if (b * kLanes + lane < len)
+            v = *reinterpret_cast<const u4*>(src_rows + (size_t)(row0 + lane) * row_bytes + (size_t)c * 16);
+        dst[u] = v;
+    }
+}
+
+// Inverse of k_relayout for one list (debug read-back).
+__global__ __launch_bounds__(256) void k_unlayout(const char* __restrict__ blocks, int64_t len,
+                                                  int row_bytes, char* __restrict__ dst_rows) {
+    const int64_t b = blockIdx.x;
+    const int nchunk = row_bytes / 16;
+    const u4* src = reinterpret_cast<const u4*>(blocks + (size_t)b * kLanes * (size_t)row_bytes);
+    for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
+        int c = u / kLanes, lane = u % kLanes;
+        if (b * kLanes + lane < len)
+            *reinterpret_cast<u4*>(dst_rows + (size_t)(b * kLanes + lane) * row_bytes + (size_t)c * 16) = src[u];
+    }
+}
+
+__global__ void k_iota_u32(uint32_t* __restrict__ p, size_t n) {
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    if (i < n) p[i] = (uint32_t)i;
+}
+
+// rank_of_pos[pos_sorted[r]] = r
+__global__ void k_scatter_rank(const uint32_t* __restrict__ pos_sorted, uint32_t* __restrict__ rank_of_pos,
+                               size_t n) {
+    size_t r = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    if (r < n) rank_of_pos[pos_sorted[r]] = (uint32_t)r;
+}
+
+// ids[pos] = id_sorted[rank_of_pos[pos]] for pos in [pos_begin, pos_begin+count)
+__global__ void k_gather_ids(const int64_t* __restrict__ id_sorted, const uint32_t* __restrict__ rank_of_pos,
+                             int64_t pos_begin, int64_t count, int64_t* __restrict__ out) {
+    int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+    if (i < count) out[i] = id_sorted[rank_of_pos[pos_begin + i]];
+}
+
+}  // namespace ivf

@@ -1,0 +1,226 @@
+"""Thin ctypes binding over the C-ABI library (include/ivf.h).  Argument marshalling
+only: every step of the search runs in the library's HIP kernels.  There is no CPU
+fallback — if the built library is missing, loading fails loudly.
+
+Function names mirror the C entry points: `Index.upload` = ivf_index_upload,
+`Index.set_device_budget` = ivf_set_device_budget, `Index.search` = ivf_search, ...
+torch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libivf_mi355x.so")
+
+IVF_FP32, IVF_FP16 = 0, 1
+STAGES = ("coarse", "probe", "regroup", "scan", "stream", "select", "total")
+
+EXPORTS = (
+    "ivf_index_create", "ivf_index_destroy", "ivf_index_upload", "ivf_index_upload_begin",
+    "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
+    "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
+    "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
+    "ivf_set_option",
+)
+
+
+class IvfError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"ivf error {code}: {msg}")
+        self.code = code
+
+
+class Info(C.Structure):
+    _fields_ = [("d", C.c_int32), ("dtype", C.c_int32), ("nlist", C.c_int64), ("n", C.c_int64),
+                ("max_list_len", C.c_int64), ("index_bytes", C.c_int64),
+                ("device_list_bytes", C.c_int64), ("host_list_bytes", C.c_int64),
+                ("resident_lists", C.c_int64), ("scratch_bytes", C.c_int64)]
+
+
+class SearchStats(C.Structure):
+    _fields_ = [("unique_lists", C.c_int64), ("pairs", C.c_int64), ("scanned_vectors", C.c_int64),
+                ("scan_bytes", C.c_int64), ("scan_bytes_resident", C.c_int64),
+                ("scan_bytes_streamed", C.c_int64), ("scan_items", C.c_int64)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads the built HIP library; raises if it has not been built
+    (python -m paper_2504_15302_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2504_15302_amd.build` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
+    lib.ivf_index_create.argtypes = [C.POINTER(vp)]
+    lib.ivf_index_destroy.argtypes = [vp]
+    lib.ivf_index_destroy.restype = None
+    lib.ivf_index_upload.argtypes = [vp, i32, i64, i64, vp, vp, i32, vp, vp]
+    lib.ivf_index_upload_begin.argtypes = [vp, i32, i64, i64, vp, i32, vp]
+    lib.ivf_index_upload_lists.argtypes = [vp, i64, i64, vp, vp]
+    lib.ivf_index_upload_end.argtypes = [vp]
+    lib.ivf_set_device_budget.argtypes = [vp, i64]
+    lib.ivf_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    lib.ivf_last_error.restype = C.c_char_p
+    lib.ivf_get_info.argtypes = [vp, C.POINTER(Info)]
+    lib.ivf_debug_last_probes.argtypes = [vp, vp, vp]
+    lib.ivf_debug_last_coarse.argtypes = [vp, vp, vp]
+    lib.ivf_debug_read_list.argtypes = [vp, i64, vp, vp, C.POINTER(i64)]
+    lib.ivf_last_search_stats.argtypes = [vp, C.POINTER(SearchStats)]
+    lib.ivf_set_timing.argtypes = [vp, i32]
+    lib.ivf_get_stage_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.ivf_set_option.argtypes = [vp, C.c_char_p, i64]
+    for name in EXPORTS:
+        if name not in ("ivf_index_destroy", "ivf_last_error"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise IvfError(rc, load_library().ivf_last_error().decode())
+
+
+def _ptr(a) -> Optional[int]:
+    """Address of a NumPy array (host) or torch tensor (host or device)."""
+    if a is None:
+        return None
+    if isinstance(a, np.ndarray):
+        assert a.flags["C_CONTIGUOUS"]
+        return a.ctypes.data
+    assert a.is_contiguous()
+    return a.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _dtype_code(a) -> int:
+    name = str(a.dtype)
+    if name.endswith("float32"):
+        return IVF_FP32
+    if name.endswith("float16"):
+        return IVF_FP16
+    raise TypeError(f"vectors must be float32 or float16, got {a.dtype}")
+
+
+class Index:
+    """Owner of one `ivf_index*`."""
+
+    def __init__(self):
+        self._lib = load_library()
+        h = C.c_void_p()
+        _check(self._lib.ivf_index_create(C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ivf_index_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- upload
+    def upload(self, centroids, vectors, ids, list_offsets):
+        nlist, d = centroids.shape
+        n = vectors.shape[0]
+        assert vectors.shape[1] == d and ids.shape[0] == n and list_offsets.shape[0] == nlist + 1
+        _check(self._lib.ivf_index_upload(self._h, d, nlist, n, _ptr(centroids), _ptr(vectors),
+                                          _dtype_code(vectors), _ptr(ids), _ptr(list_offsets)))
+
+    def upload_begin(self, centroids, n: int, dtype: int, list_offsets):
+        nlist, d = centroids.shape
+        _check(self._lib.ivf_index_upload_begin(self._h, d, nlist, n, _ptr(centroids), dtype,
+                                                _ptr(list_offsets)))
+
+    def upload_lists(self, list_begin: int, list_end: int, vectors, ids):
+        _check(self._lib.ivf_index_upload_lists(self._h, list_begin, list_end, _ptr(vectors), _ptr(ids)))
+
+    def upload_end(self):
+        _check(self._lib.ivf_index_upload_end(self._h))
+
+    # ---- placement
+    def set_device_budget(self, nbytes: int):
+        _check(self._lib.ivf_set_device_budget(self._h, int(nbytes)))
+
+    # ---- search
+    def search(self, queries, nprobe: int, k: int, out_ids=None, out_scores=None, stream=None):
+        """queries: float32 CUDA tensor [nq, d].  Returns (ids int64 [nq,k], scores
+        float32 [nq,k]) CUDA tensors; valid once `stream` (default: torch's current
+        stream) has been synchronised."""
+        import torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        nq = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        if out_scores is None:
+            out_scores = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        _check(self._lib.ivf_search(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
+                                    _ptr(out_scores), _stream_handle(stream)))
+        return out_ids, out_scores
+
+    def search_raw(self, queries_ptr, nq, nprobe, k, out_ids_ptr, out_scores_ptr, stream_ptr=None) -> int:
+        """The C call with raw addresses, returning the status code (for error-path tests)."""
+        return self._lib.ivf_search(self._h, queries_ptr, nq, nprobe, k, out_ids_ptr, out_scores_ptr, stream_ptr)
+
+    # ---- introspection
+    def info(self) -> Info:
+        out = Info()
+        _check(self._lib.ivf_get_info(self._h, C.byref(out)))
+        return out
+
+    def last_probes(self, nq: int, nprobe: int, stream=None):
+        import torch
+        out = torch.empty((nq, nprobe), dtype=torch.int32, device="cuda")
+        _check(self._lib.ivf_debug_last_probes(self._h, _ptr(out), _stream_handle(stream)))
+        return out
+
+    def last_coarse(self, nq: int, nlist: int, stream=None):
+        import torch
+        out = torch.empty((nq, nlist), dtype=torch.float32, device="cuda")
+        _check(self._lib.ivf_debug_last_coarse(self._h, _ptr(out), _stream_handle(stream)))
+        return out
+
+    def read_list(self, list_no: int, d: int, dtype: int):
+        ln = C.c_int64()
+        _check(self._lib.ivf_debug_read_list(self._h, list_no, None, None, C.byref(ln)))
+        vec = np.empty((ln.value, d), dtype=np.float16 if dtype == IVF_FP16 else np.float32)
+        ids = np.empty(ln.value, dtype=np.int64)
+        _check(self._lib.ivf_debug_read_list(self._h, list_no, _ptr(vec), _ptr(ids), C.byref(ln)))
+        return vec, ids
+
+    def last_search_stats(self) -> SearchStats:
+        out = SearchStats()
+        _check(self._lib.ivf_last_search_stats(self._h, C.byref(out)))
+        return out
+
+    def set_timing(self, enable: bool):
+        _check(self._lib.ivf_set_timing(self._h, int(enable)))
+
+    def stage_ms(self) -> dict:
+        arr = (C.c_float * len(STAGES))()
+        _check(self._lib.ivf_get_stage_ms(self._h, arr))
+        return {name: float(arr[i]) for i, name in enumerate(STAGES)}
+
+    def set_option(self, name: str, value: int):
+        _check(self._lib.ivf_set_option(self._h, name.encode(), int(value)))

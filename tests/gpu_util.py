@@ -1,0 +1,150 @@
+"""Helpers of the GPU parity tests: run the HIP path through the C ABI binding and
+compare it with the CPU oracle under the benchmark's correctness bar."""
+from __future__ import annotations
+
+import sys
+import time
+
+import numpy as np
+
+from oracle import check as CK
+from oracle import ivf_oracle as O
+from paper_2504_15302_amd import ivf
+from paper_2504_15302_amd import workloads as W
+
+
+def say(msg: str):
+    """Progress line, flushed: names the case before each GPU step."""
+    print(f"[gpu-test] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def gpu_search(index: ivf.Index, q: np.ndarray, nprobe: int, k: int):
+    import torch
+    qd = torch.from_numpy(np.ascontiguousarray(q, dtype=np.float32)).cuda()
+    ids, scores = index.search(qd, nprobe, k)
+    torch.cuda.synchronize()
+    nprobe_eff = min(nprobe, index.info().nlist)
+    probes = index.last_probes(q.shape[0], nprobe_eff)
+    coarse = index.last_coarse(q.shape[0], index.info().nlist)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), scores.cpu().numpy(), probes.cpu().numpy(), coarse.cpu().numpy()
+
+
+def check_against_oracle(cen, vec, ids, off, q, nprobe, k, got, storage: str, extra_rows: int = 8,
+                         abs_floor: float = 0.0, coarse_only_lists=None):
+    """`got` = (ids, scores, probes, coarse) from gpu_search.  The index arrays are host
+    NumPy arrays holding (at least) every probed list; list numbers are global."""
+    g_ids, g_scores, g_probes, g_coarse = got
+    nlist = cen.shape[0]
+    nprobe = min(nprobe, nlist)
+    o_coarse = O.coarse(q, cen)
+    # stage 1: coarse scores, fp32 MFMA vs fp64: error bounded by ~d*eps*|q||c|
+    scale = np.linalg.norm(q.astype(np.float64), axis=1)[:, None] * \
+        np.linalg.norm(cen.astype(np.float64), axis=1)[None, :]
+    err = np.abs(g_coarse.astype(np.float64) - o_coarse)
+    assert (err <= 1e-5 * np.maximum(scale, 1e-30)).all(), \
+        f"coarse scores off by up to {float((err / np.maximum(scale, 1e-30)).max()):.3g} of |q||c|"
+    # stage 2: probe sets (order inside the set is checked when sets are equal)
+    same = CK.check_probes(g_probes, o_coarse, nprobe)
+    o_probes = O.probe_select(o_coarse, nprobe)
+    if same:
+        for r in range(q.shape[0]):
+            if not np.array_equal(g_probes[r], o_probes[r]):
+                # only near-tied neighbours may swap
+                for a, b in zip(g_probes[r], o_probes[r]):
+                    if a != b:
+                        assert CK._near(float(o_coarse[r, a]), float(o_coarse[r, b]), CK.TIE_REL), \
+                            f"q{r}: probe order differs beyond a near-tie"
+        use = o_probes
+    else:
+        use = g_probes     # accepted near-tie at the probe boundary: oracle re-scans the GPU's set
+    # stage 3: scan + selection
+    o_ids, o_scores = O.scan_select(vec, ids, off, q, use, k + extra_rows)
+    res = CK.check_topk(g_ids, g_scores, o_ids, o_scores, k, CK.SCORE_REL[storage], abs_floor=abs_floor)
+    CK.check_ids_in_probed_lists(g_ids, use, ids, off)
+    return res
+
+
+def upload_host_index(h: W.HostIndex) -> ivf.Index:
+    idx = ivf.Index()
+    idx.upload(h.centroids, h.vectors, h.ids, h.offsets)
+    return idx
+
+
+class DeviceWorkload:
+    """A large synthetic index generated on the GPU and handed to the library piece by
+    piece, plus what the oracle needs to re-derive any list on the host."""
+
+    def __init__(self, w: W.Workload, groups_per_chunk: int = 16):
+        import torch
+        self.w = w
+        t0 = time.time()
+        self.cen = W.centroids(w)
+        self.off = W.list_offsets(w)
+        self.cen_dev = torch.from_numpy(self.cen).cuda()
+        self.ids_dev = W.user_ids_device(w)
+        self.index = ivf.Index()
+        dt = ivf.IVF_FP16 if w.storage == "fp16" else ivf.IVF_FP32
+        self.index.upload_begin(self.cen, w.n, dt, self.off)
+        for l0, l1, vec in W.iter_device_chunks(w, self.cen_dev, self.off, groups_per_chunk):
+            r0, r1 = int(self.off[l0]), int(self.off[l1])
+            self.index.upload_lists(l0, l1, vec, self.ids_dev[r0:r1].contiguous())
+            del vec
+        self.index.upload_end()
+        torch.cuda.synchronize()
+        say(f"{w.name}: generated and uploaded {w.n} x {w.d} {w.storage} in {time.time() - t0:.1f}s")
+
+    def host_lists(self, lists):
+        """Row-major host copy of the given lists, regenerated from the seeded recipe
+        (not read back from the library): a compact sub-index (vectors, ids, offsets,
+        global->compact map)."""
+        lists = sorted(set(int(l) for l in lists))
+        by_group = {}
+        for l in lists:
+            by_group.setdefault(l // W.GROUP, []).append(l)
+        parts, idp, lens = {}, {}, {}
+        for g, ls in by_group.items():
+            gv = W.group_vectors_device(self.w, self.cen_dev, self.off, g, g + 1)
+            base = int(self.off[g * W.GROUP])
+            for l in ls:
+                a, b = int(self.off[l]) - base, int(self.off[l + 1]) - base
+                parts[l] = gv[a:b].cpu().numpy()
+                idp[l] = self.ids_dev[int(self.off[l]):int(self.off[l + 1])].cpu().numpy()
+                lens[l] = b - a
+            del gv
+        coff = np.zeros(len(lists) + 1, dtype=np.int64)
+        np.cumsum([lens[l] for l in lists], out=coff[1:])
+        vec = np.concatenate([parts[l] for l in lists], axis=0) if lists else \
+            np.empty((0, self.w.d), dtype=np.float16 if self.w.storage == "fp16" else np.float32)
+        ids = np.concatenate([idp[l] for l in lists]) if lists else np.empty(0, np.int64)
+        cmap = {l: i for i, l in enumerate(lists)}
+        return vec, ids, coff, cmap
+
+
+def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, rows=None, extra_rows: int = 8):
+    """Parity at full size: coarse scores and probe sets for every query (centroids are
+    small), scan + selection for the query rows in `rows` (all if None), with only the
+    probed lists brought to the host."""
+    g_ids, g_scores, g_probes, g_coarse = got
+    w = dw.w
+    nprobe = min(nprobe, w.nlist)
+    o_coarse = O.coarse(q, dw.cen)
+    scale = np.linalg.norm(q.astype(np.float64), axis=1)[:, None] * \
+        np.linalg.norm(dw.cen.astype(np.float64), axis=1)[None, :]
+    err = np.abs(g_coarse.astype(np.float64) - o_coarse)
+    assert (err <= 1e-5 * np.maximum(scale, 1e-30)).all(), "coarse scores off"
+    same = CK.check_probes(g_probes, o_coarse, nprobe)
+    use = O.probe_select(o_coarse, nprobe) if same else g_probes
+    rows = list(range(q.shape[0])) if rows is None else list(rows)
+    vec, ids, coff, cmap = dw.host_lists(use[rows].ravel())
+    cprobes = np.vectorize(cmap.get)(use[rows]).astype(np.int32)
+    o_ids, o_scores = O.scan_select(vec, ids, coff, q[rows], cprobes, k + extra_rows)
+    res = CK.check_topk(g_ids[rows], g_scores[rows], o_ids, o_scores, k, CK.SCORE_REL[w.storage])
+    CK.check_ids_in_probed_lists(g_ids[rows], cprobes, ids, coff)
+    # properties that hold for every row at any size
+    assert np.all(g_scores[:, :-1] >= g_scores[:, 1:])
+    for r in range(q.shape[0]):
+        real = g_ids[r][g_ids[r] >= 0]
+        assert len(np.unique(real)) == len(real)
+    return res

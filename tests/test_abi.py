@@ -1,0 +1,54 @@
+"""CPU-side checks of the C-ABI boundary: the built library loads, exports every
+symbol include/ivf.h declares, and fails with an error code (not a crash) where no
+GPU is present."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2504_15302_amd import ivf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ivf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ivf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_all_exported_and_bound():
+    lib = ivf.load_library()
+    declared = _declared_symbols()
+    assert "ivf_search" in declared and "ivf_index_upload" in declared and "ivf_set_device_budget" in declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in ivf.h but not exported"
+    assert sorted(ivf.EXPORTS) == declared
+
+
+def test_info_and_stats_structs_match_header_layout():
+    assert C.sizeof(ivf.Info) == 8 + 8 * 8
+    assert C.sizeof(ivf.SearchStats) == 7 * 8
+
+
+def test_null_arguments_return_error_codes_without_a_gpu():
+    lib = ivf.load_library()
+    assert lib.ivf_index_create(None) == -1
+    assert b"NULL" in lib.ivf_last_error()
+    assert lib.ivf_search(None, None, 1, 1, 1, None, None, None) == -1
+    assert lib.ivf_set_device_budget(None, 0) == -1
+    assert lib.ivf_index_upload_end(None) == -1
+    assert lib.ivf_set_option(None, b"scan_mode", 0) == -1
+    lib.ivf_index_destroy(None)   # allowed
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_15302_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("the oracle's tests", "").replace("CPU oracle", "") \
+                    or f == "workloads.py", f"{f} mentions the oracle"
+                assert "import oracle" not in text and "from oracle" not in text

@@ -1,0 +1,257 @@
+"""GPU parity, small sizes: the HIP path (through the C ABI) against the CPU oracle,
+element by element, on seeded inputs that span several 64-vector blocks, ragged tails,
+empty lists, shared lists and the degenerate cases of the method."""
+import numpy as np
+import pytest
+
+from oracle import check as CK
+from oracle import ivf_oracle as O
+from paper_2504_15302_amd import ivf
+from paper_2504_15302_amd import workloads as W
+from tests.golden_util import load_basis_case
+from tests.gpu_util import (check_against_oracle, gpu_search, say, upload_host_index)
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_index(seed, n, d, nlist, storage, empty_lists=(), normalise=False):
+    rng = np.random.default_rng(seed)
+    cen = rng.standard_normal((nlist, d)).astype(np.float32)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    if normalise:
+        cen /= np.linalg.norm(cen, axis=1, keepdims=True)
+        x /= np.linalg.norm(x, axis=1, keepdims=True)
+    sc = x.astype(np.float64) @ cen.astype(np.float64).T
+    sc[:, list(empty_lists)] = -np.inf
+    lab = np.argmax(sc, axis=1)
+    order = np.argsort(lab, kind="stable")
+    x, lab = x[order], lab[order]
+    off = np.zeros(nlist + 1, dtype=np.int64)
+    np.cumsum(np.bincount(lab, minlength=nlist), out=off[1:])
+    ids = rng.permutation(7 * n + 13)[:n].astype(np.int64)          # unique, not contiguous
+    vec = np.ascontiguousarray(x.astype(np.float16 if storage == "fp16" else np.float32))
+    return cen, vec, ids, off
+
+
+def _floor(q, vec):
+    return float(np.linalg.norm(q, axis=1).max() * np.linalg.norm(vec.astype(np.float32), axis=1).max())
+
+
+@pytest.fixture(scope="module")
+def c1():
+    w = W.CONFIGS["C1"]
+    h = W.build_host_index(w)
+    say("C1: uploading 100k x 384 fp32")
+    return w, h, upload_host_index(h)
+
+
+def test_c1_matches_oracle(c1):
+    w, h, idx = c1
+    q = W.queries(w)
+    say("C1: search nq=16 nprobe=8 k=10")
+    got = gpu_search(idx, q, w.nprobe, w.k)
+    res = check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, w.k, got, w.storage)
+    say(f"C1 ok: {res}")
+    st = idx.last_search_stats()
+    o_probes = O.probe_select(O.coarse(q, h.centroids), w.nprobe)
+    uniq = np.unique(o_probes)
+    assert st.unique_lists == len(uniq) and st.pairs == w.nq * w.nprobe
+    assert st.scanned_vectors == int(np.diff(h.offsets)[uniq].sum())
+    assert st.scan_bytes == st.scanned_vectors * w.d * 4 and st.scan_bytes_streamed == 0
+
+
+@pytest.mark.parametrize("k,nprobe,nq", [(1, 1, 1), (5, 3, 7), (100, 8, 16), (1024, 256, 3), (10, 300, 5)])
+def test_c1_other_k_nprobe_nq(c1, k, nprobe, nq):
+    w, h, idx = c1
+    q = W.queries(w, batch=3, nq=nq)
+    say(f"C1 variants: nq={nq} nprobe={nprobe} k={k}")
+    got = gpu_search(idx, q, nprobe, k)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, nprobe, k, got, w.storage)
+
+
+def test_rows_do_not_depend_on_the_batch(c1):
+    w, h, idx = c1
+    q = W.queries(w, batch=1)
+    full = gpu_search(idx, q, w.nprobe, w.k)
+    for r in (0, 5, 15):
+        say(f"C1 batch independence: row {r} alone")
+        one = gpu_search(idx, q[r:r + 1], w.nprobe, w.k)
+        assert np.array_equal(one[0][0], full[0][r]) and np.array_equal(one[1][0], full[1][r])
+    rev = gpu_search(idx, q[::-1].copy(), w.nprobe, w.k)
+    assert np.array_equal(rev[0][::-1], full[0]) and np.array_equal(rev[1][::-1], full[1])
+
+
+@pytest.mark.parametrize("storage", ["fp32", "fp16"])
+def test_golden_basis_case_on_gpu(storage):
+    g = load_basis_case(np.float16 if storage == "fp16" else np.float32)
+    pad = 8 - g["d"]
+    cen = np.pad(g["centroids"], ((0, 0), (0, pad)))
+    vec = np.ascontiguousarray(np.pad(g["vectors"], ((0, 0), (0, pad))))
+    idx = ivf.Index()
+    idx.upload(np.ascontiguousarray(cen), vec, g["ids"], g["offsets"])
+    for e in g["expects"]:
+        q = np.pad(g["queries"][e["query"]], (0, pad))[None, :].astype(np.float32)
+        say(f"golden basis case {storage}: {e['query']} nprobe={e['nprobe']} k={e['k']}")
+        ids, scores, probes, coarse = gpu_search(idx, q, e["nprobe"], e["k"])
+        assert probes[0].tolist() == e["probes"]
+        assert ids[0].tolist() == e["ids"]                     # includes the id tie-break and the padding
+        assert scores[0].tolist() == e["scores"]               # exact in binary
+    idx.close()
+
+
+CASES = [
+    # name, n, d, nlist, storage, nq, nprobe, k, empty lists
+    ("tiny_d8", 50, 8, 3, "fp32", 4, 2, 5, ()),
+    ("one_vector", 1, 16, 1, "fp16", 2, 1, 3, ()),
+    ("ragged_d72", 3000, 72, 7, "fp16", 9, 3, 10, ()),
+    ("ragged_d40_fp32", 3000, 40, 7, "fp32", 9, 3, 10, ()),
+    ("empty_lists", 2000, 32, 12, "fp32", 6, 12, 8, (0, 5, 11)),
+    ("k_above_candidates", 300, 24, 6, "fp32", 5, 2, 400, ()),
+    ("all_lists", 5000, 64, 33, "fp16", 8, 33, 20, ()),
+    ("many_blocks", 40000, 128, 5, "fp16", 6, 2, 50, ()),
+    ("wide_d1024", 1500, 1024, 4, "fp32", 3, 2, 10, ()),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_edge_cases_match_oracle(case):
+    name, n, d, nlist, storage, nq, nprobe, k, empty = case
+    cen, vec, ids, off = _random_index(hash(name) % 1000, n, d, nlist, storage, empty)
+    rng = np.random.default_rng(99)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    idx = ivf.Index()
+    idx.upload(cen, vec, ids, off)
+    say(f"edge case {name}")
+    got = gpu_search(idx, q, nprobe, k)
+    check_against_oracle(cen, vec, ids, off, q, nprobe, k, got, storage, abs_floor=_floor(q, vec))
+    idx.close()
+
+
+def test_many_queries_share_one_list():
+    """More than kQB queries on the same list: several query groups per block."""
+    cen, vec, ids, off = _random_index(5, 6000, 64, 4, "fp16", normalise=True)
+    rng = np.random.default_rng(1)
+    base = cen[2]
+    q = (base[None, :] + 0.05 * rng.standard_normal((23, 64))).astype(np.float32)
+    idx = ivf.Index()
+    idx.upload(cen, vec, ids, off)
+    say("23 queries probing the same lists")
+    got = gpu_search(idx, q, 2, 15)
+    check_against_oracle(cen, vec, ids, off, q, 2, 15, got, "fp16")
+    st = idx.last_search_stats()
+    assert st.unique_lists <= 4 and st.pairs == 46
+    idx.close()
+
+
+def test_exact_ties_go_to_the_smaller_id():
+    d = 16
+    rng = np.random.default_rng(8)
+    v = rng.standard_normal(d).astype(np.float32)
+    rows = [v, v, v * 0.5, v, v * 0.25, v]
+    vec = np.stack(rows).astype(np.float32)
+    ids = np.array([90, 40, 10, 70, 5, 41], dtype=np.int64)
+    off = np.array([0, 3, 6], dtype=np.int64)
+    cen = np.stack([v, v * 0.9]).astype(np.float32)
+    idx = ivf.Index()
+    idx.upload(cen, vec, ids, off)
+    say("exact score ties across two lists")
+    gi, gs, _, _ = gpu_search(idx, v[None, :], 2, 6)
+    oi, os_, _, _ = O.search(cen, vec, ids, off, v[None, :], 2, 6)
+    assert gi[0].tolist() == oi[0].tolist() == [40, 41, 70, 90, 10, 5]
+    assert gs[0, 0] == gs[0, 3]
+    idx.close()
+
+
+def test_upload_in_pieces_and_from_device_memory_equals_one_shot(c1):
+    import torch
+    w, h, idx = c1
+    q = W.queries(w, batch=2)
+    ref = gpu_search(idx, q, w.nprobe, w.k)
+    say("C1 uploaded in pieces from device memory")
+    idx2 = ivf.Index()
+    idx2.upload_begin(h.centroids, w.n, ivf.IVF_FP32, h.offsets)
+    cuts = [0, 1, 64, 65, 200, 256]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        r0, r1 = int(h.offsets[a]), int(h.offsets[b])
+        vd = torch.from_numpy(h.vectors[r0:r1]).cuda()
+        idd = torch.from_numpy(h.ids[r0:r1]).cuda()
+        idx2.upload_lists(a, b, vd, idd)
+    idx2.upload_end()
+    got = gpu_search(idx2, q, w.nprobe, w.k)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    for l in (0, 17, 255):
+        vec, ids = idx2.read_list(l, w.d, ivf.IVF_FP32)
+        assert np.array_equal(vec, h.vectors[h.offsets[l]:h.offsets[l + 1]])
+        assert np.array_equal(ids, h.ids[h.offsets[l]:h.offsets[l + 1]])
+    idx2.close()
+
+
+def test_results_do_not_depend_on_placement(c1):
+    w, h, idx = c1
+    q = W.queries(w, batch=4)
+    ref = gpu_search(idx, q, w.nprobe, w.k)
+    total = idx.info().index_bytes
+    for frac in (0.25, 0.0, 0.6, 1.0):
+        say(f"C1 device budget {frac:.2f} of the index")
+        idx.set_device_budget(int(total * frac))
+        info = idx.info()
+        assert info.device_list_bytes <= int(total * frac)
+        assert info.device_list_bytes + info.host_list_bytes == total
+        got = gpu_search(idx, q, w.nprobe, w.k)
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+        st = idx.last_search_stats()
+        assert st.scan_bytes_resident + st.scan_bytes_streamed == st.scan_bytes
+        if frac == 0.0:
+            assert st.scan_bytes_resident == 0 and info.resident_lists == 0
+        for l in (3, 100):
+            vec, ids = idx.read_list(l, w.d, ivf.IVF_FP32)
+            assert np.array_equal(vec, h.vectors[h.offsets[l]:h.offsets[l + 1]])
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, w.k, ref, w.storage)
+
+
+def test_scan_launch_options_agree(c1):
+    w, h, idx = c1
+    q = W.queries(w, batch=5)
+    ref = gpu_search(idx, q, w.nprobe, w.k)
+    try:
+        for mode in (0, 1):
+            for unroll in (4, 8, 16):
+                say(f"C1 scan_mode={mode} scan_unroll={unroll}")
+                idx.set_option("scan_mode", mode)
+                idx.set_option("scan_unroll", unroll)
+                got = gpu_search(idx, q, w.nprobe, w.k)
+                assert np.array_equal(got[0], ref[0])
+                assert np.allclose(got[1], ref[1], rtol=1e-6)
+    finally:
+        idx.set_option("scan_mode", 0)
+        idx.set_option("scan_unroll", 8)
+
+
+def test_error_paths_on_the_gpu(c1):
+    import torch
+    w, h, idx = c1
+    q = torch.zeros((2, w.d), device="cuda")
+    oi = torch.empty((2, 4), dtype=torch.int64, device="cuda")
+    os_ = torch.empty((2, 4), dtype=torch.float32, device="cuda")
+    assert idx.search_raw(None, 2, 1, 4, oi.data_ptr(), os_.data_ptr()) == -1
+    assert idx.search_raw(q.data_ptr(), 2, 0, 4, oi.data_ptr(), os_.data_ptr()) == -1
+    assert idx.search_raw(q.data_ptr(), 2, 1, 0, oi.data_ptr(), os_.data_ptr()) == -1
+    assert idx.search_raw(q.data_ptr(), 2, 1, 5000, oi.data_ptr(), os_.data_ptr()) == -5
+    assert idx.search_raw(q.data_ptr(), -1, 1, 4, oi.data_ptr(), os_.data_ptr()) == -1
+    assert idx.search_raw(q.data_ptr(), 0, 1, 4, oi.data_ptr(), os_.data_ptr()) == 0
+    with pytest.raises(ivf.IvfError):
+        idx.set_device_budget(-1)
+    with pytest.raises(ivf.IvfError):
+        idx.set_option("no_such_option", 1)
+    empty = ivf.Index()
+    assert empty.search_raw(q.data_ptr(), 2, 1, 4, oi.data_ptr(), os_.data_ptr()) == -1
+    with pytest.raises(ivf.IvfError):      # d not a multiple of 8
+        empty.upload(np.zeros((2, 12), np.float32), np.zeros((4, 12), np.float32),
+                     np.arange(4, dtype=np.int64), np.array([0, 2, 4], dtype=np.int64))
+    with pytest.raises(ivf.IvfError):      # offsets do not end at n
+        empty.upload(np.zeros((2, 16), np.float32), np.zeros((4, 16), np.float32),
+                     np.arange(4, dtype=np.int64), np.array([0, 2, 3], dtype=np.int64))
+    empty.close()
+    # the index still works after the failed calls
+    got = gpu_search(idx, W.queries(w), w.nprobe, w.k)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, W.queries(w), w.nprobe, w.k, got, w.storage)
