@@ -202,8 +202,11 @@ __global__ __launch_bounds__(kScanWaves * 64) void k_scan(
         scan_dispatch<HALF, U>(it, Q, pair_q, d, scores, bmax, lane);
     } else {
         for (;;) {
-            uint32_t t = 0;
-            if (lane == 0) t = atomicAdd(queue, 1u);
+            // All 64 lanes take part in the atomic (lane 0 adds 1, the others 0) so that
+            // no divergent branch surrounds the wave-uniform read below: with the ticket
+            // taken under `if (lane == 0)` the compiler split the loop per lane and the
+            // other 63 lanes kept re-running item 0.
+            uint32_t t = atomicAdd(queue, lane == 0 ? 1u : 0u);
             t = __builtin_amdgcn_readfirstlane(t);
             if (t >= T) break;           // every wavefront reaches this: the queue only grows
             ScanItem it = items[t];

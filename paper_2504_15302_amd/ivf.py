@@ -61,6 +61,10 @@ def load_library() -> C.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2504_15302_amd.build` "
             "(there is no CPU fallback)")
+    # torch ships its own HIP runtime under the same SONAME.  Import it first so that
+    # the library binds to the runtime torch already loaded: two HIP runtimes in one
+    # process do not both see the GPU.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
     lib.ivf_index_create.argtypes = [C.POINTER(vp)]
