@@ -163,9 +163,10 @@ typedef struct {
 /* Statistics of the last search; synchronises the stream it ran on. */
 int ivf_last_search_stats(ivf_index *idx, ivf_search_stats *out);
 
-/* Stage timing with HIP events on the search's own stream.  When enabled, every
-   search records events around its stages; ivf_get_stage_ms synchronises and returns
-   the last search's times in milliseconds. */
+/* Stage timing with HIP events on the search's own stream.  While enabled, every
+   search records events around its stages (the events of the last 64 searches are
+   kept); ivf_get_stage_ms waits for the search `back` calls ago (0 = the last one) and
+   returns its stage times in milliseconds. */
 enum {
     IVF_STAGE_COARSE = 0,   /* centroid GEMM + tile maxima */
     IVF_STAGE_PROBE = 1,    /* top-nprobe selection */
@@ -177,7 +178,7 @@ enum {
     IVF_NUM_STAGES = 7
 };
 int ivf_set_timing(ivf_index *idx, int enable);
-int ivf_get_stage_ms(ivf_index *idx, float *ms /* [IVF_NUM_STAGES] host */);
+int ivf_get_stage_ms(ivf_index *idx, int back, float *ms /* [IVF_NUM_STAGES] host */);
 
 /* Tuning knobs for experiments (launch shape of the scan kernel etc.); unknown names
    return IVF_ERR_INVALID.  Defaults are the tuned values. */

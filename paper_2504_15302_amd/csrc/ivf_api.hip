@@ -95,6 +95,8 @@ struct Scratch {
 };
 
 constexpr int kMaxStage = 8;
+constexpr int kTimingSlots = 64;   // searches whose stage events are kept
+constexpr int kEvPerSearch = 7;    // stage boundaries 0..6
 
 }  // namespace
 
@@ -142,8 +144,9 @@ struct ivf_index {
     bool last_offload = false;
     ivf_search_stats last_stats = {};
     bool timing = false;
-    hipEvent_t ev[IVF_NUM_STAGES + 1] = {};
-    bool ev_valid = false;
+    hipEvent_t ev[kTimingSlots][kEvPerSearch] = {};
+    bool ev_created = false;
+    int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
     int64_t opt_scan_mode = 0, opt_scan_unroll = 8, opt_scan_wgs_per_cu = 2, opt_stage_mb = 64,
             opt_nstage = 3;
@@ -459,7 +462,6 @@ int ivf_index_create(ivf_index** out) {
         e = hipEventCreateWithFlags(&x->stage_ready[i], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&x->stage_free[i], hipEventDisableTiming);
     }
-    for (int i = 0; e == hipSuccess && i <= IVF_NUM_STAGES; ++i) e = hipEventCreate(&x->ev[i]);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         int rc = fail(IVF_ERR_HIP, "index creation failed: %s", hipGetErrorString(e));
@@ -482,8 +484,9 @@ void ivf_index_destroy(ivf_index* x) {
         if (x->stage_ready[i]) (void)hipEventDestroy(x->stage_ready[i]);
         if (x->stage_free[i]) (void)hipEventDestroy(x->stage_free[i]);
     }
-    for (int i = 0; i <= IVF_NUM_STAGES; ++i)
-        if (x->ev[i]) (void)hipEventDestroy(x->ev[i]);
+    for (int sl = 0; sl < kTimingSlots; ++sl)
+        for (int i = 0; i < kEvPerSearch; ++i)
+            if (x->ev[sl][i]) (void)hipEventDestroy(x->ev[sl][i]);
     delete x;
 }
 
@@ -791,8 +794,9 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     const int ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
     const int npairs = (int)(nq * nprobe);
     const bool tm = x->timing;
+    hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
     int evi = 0;
-    auto mark = [&]() { if (tm) (void)hipEventRecord(x->ev[evi], st); ++evi; };
+    auto mark = [&]() { if (tm) (void)hipEventRecord(evs[evi], st); ++evi; };
 
     mark();   // 0
     {
@@ -861,7 +865,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     x->last_nprobe = nprobe;
     x->last_stream = st;
     x->last_offload = offload;
-    x->ev_valid = tm;
+    if (tm) x->timed_searches += 1;
     return 0;
 }
 
@@ -972,19 +976,26 @@ int ivf_last_search_stats(ivf_index* x, ivf_search_stats* out) {
 
 int ivf_set_timing(ivf_index* x, int enable) {
     if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
+    if (enable && !x->ev_created) {
+        for (int sl = 0; sl < kTimingSlots; ++sl)
+            for (int i = 0; i < kEvPerSearch; ++i) HIP_TRY(hipEventCreate(&x->ev[sl][i]));
+        x->ev_created = true;
+    }
     x->timing = enable != 0;
-    x->ev_valid = false;
+    x->timed_searches = 0;
     return 0;
 }
 
-int ivf_get_stage_ms(ivf_index* x, float* ms) {
+int ivf_get_stage_ms(ivf_index* x, int back, float* ms) {
     int rc = check_ready(x);
     if (rc) return rc;
     if (!ms) return fail(IVF_ERR_INVALID, "ms is NULL");
-    if (!x->ev_valid) return fail(IVF_ERR_INVALID, "timing was not enabled for the last search");
-    HIP_TRY(hipEventSynchronize(x->ev[6]));
-    for (int i = 0; i < 6; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], x->ev[i], x->ev[i + 1]));
-    HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_TOTAL], x->ev[0], x->ev[6]));
+    if (back < 0 || back >= kTimingSlots || back >= x->timed_searches)
+        return fail(IVF_ERR_INVALID, "no timed search %d calls back (kept: %d)", back, kTimingSlots);
+    hipEvent_t* evs = x->ev[(x->timed_searches - 1 - back) % kTimingSlots];
+    HIP_TRY(hipEventSynchronize(evs[6]));
+    for (int i = 0; i < 6; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], evs[i], evs[i + 1]));
+    HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_TOTAL], evs[0], evs[6]));
     return 0;
 }
 

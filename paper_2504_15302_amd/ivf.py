@@ -83,7 +83,7 @@ def load_library() -> C.CDLL:
     lib.ivf_debug_read_list.argtypes = [vp, i64, vp, vp, C.POINTER(i64)]
     lib.ivf_last_search_stats.argtypes = [vp, C.POINTER(SearchStats)]
     lib.ivf_set_timing.argtypes = [vp, i32]
-    lib.ivf_get_stage_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.ivf_get_stage_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
     lib.ivf_set_option.argtypes = [vp, C.c_char_p, i64]
     for name in EXPORTS:
         if name not in ("ivf_index_destroy", "ivf_last_error"):
@@ -221,9 +221,10 @@ class Index:
     def set_timing(self, enable: bool):
         _check(self._lib.ivf_set_timing(self._h, int(enable)))
 
-    def stage_ms(self) -> dict:
+    def stage_ms(self, back: int = 0) -> dict:
+        """Stage times (ms) of the timed search `back` calls ago (0 = the last one)."""
         arr = (C.c_float * len(STAGES))()
-        _check(self._lib.ivf_get_stage_ms(self._h, arr))
+        _check(self._lib.ivf_get_stage_ms(self._h, back, arr))
         return {name: float(arr[i]) for i, name in enumerate(STAGES)}
 
     def set_option(self, name: str, value: int):

@@ -3,7 +3,6 @@ compare it with the CPU oracle under the benchmark's correctness bar."""
 from __future__ import annotations
 
 import sys
-import time
 
 import numpy as np
 
@@ -77,23 +76,12 @@ class DeviceWorkload:
     piece, plus what the oracle needs to re-derive any list on the host."""
 
     def __init__(self, w: W.Workload, groups_per_chunk: int = 16):
-        import torch
+        from paper_2504_15302_amd.loader import load_workload
+        lw = load_workload(w, groups_per_chunk, log=say)
         self.w = w
-        t0 = time.time()
-        self.cen = W.centroids(w)
-        self.off = W.list_offsets(w)
-        self.cen_dev = torch.from_numpy(self.cen).cuda()
-        self.ids_dev = W.user_ids_device(w)
-        self.index = ivf.Index()
-        dt = ivf.IVF_FP16 if w.storage == "fp16" else ivf.IVF_FP32
-        self.index.upload_begin(self.cen, w.n, dt, self.off)
-        for l0, l1, vec in W.iter_device_chunks(w, self.cen_dev, self.off, groups_per_chunk):
-            r0, r1 = int(self.off[l0]), int(self.off[l1])
-            self.index.upload_lists(l0, l1, vec, self.ids_dev[r0:r1].contiguous())
-            del vec
-        self.index.upload_end()
-        torch.cuda.synchronize()
-        say(f"{w.name}: generated and uploaded {w.n} x {w.d} {w.storage} in {time.time() - t0:.1f}s")
+        self.cen, self.off = lw.centroids, lw.offsets
+        self.cen_dev, self.ids_dev, self.index = lw.centroids_dev, lw.ids_dev, lw.index
+        say(f"{w.name}: generated and uploaded {w.n} x {w.d} {w.storage} in {lw.seconds:.1f}s")
 
     def host_lists(self, lists):
         """Row-major host copy of the given lists, regenerated from the seeded recipe

@@ -1,0 +1,120 @@
+"""GPU parity at the benchmark's full sizes (C2..C5), in the launch configuration
+bench.py times.  The index is generated on the device and handed to the library in
+pieces; the oracle sees only the probed lists, regenerated from the seeded recipe and
+copied to the host.  C2 and C3 are checked on every query; C5 on sampled queries (the
+oracle computes those rows one by one) plus the properties that hold for every row."""
+import numpy as np
+import pytest
+
+from oracle import ivf_oracle as O
+from paper_2504_15302_amd import ivf
+from paper_2504_15302_amd import workloads as W
+from tests.gpu_util import DeviceWorkload, check_large, gpu_search, say
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_assignment_sample(dw, nsample_lists=24):
+    """The list a vector was generated for is its arg-max inner-product centroid."""
+    rng = np.random.default_rng(0)
+    lists = rng.choice(dw.w.nlist, size=nsample_lists, replace=False)
+    vec, ids, coff, cmap = dw.host_lists(lists)
+    take = rng.choice(vec.shape[0], size=min(2000, vec.shape[0]), replace=False)
+    lab, _ = O.assign(vec[take], dw.cen)
+    truth = np.empty(vec.shape[0], dtype=np.int32)
+    for l, c in cmap.items():
+        truth[coff[c]:coff[c + 1]] = l
+    assert np.array_equal(lab, truth[take])
+
+
+def _check_readback(dw, lists):
+    vec, ids, coff, cmap = dw.host_lists(lists)
+    dt = ivf.IVF_FP16 if dw.w.storage == "fp16" else ivf.IVF_FP32
+    for l in lists:
+        v, i = dw.index.read_list(int(l), dw.w.d, dt)
+        c = cmap[int(l)]
+        assert np.array_equal(v, vec[coff[c]:coff[c + 1]]) and np.array_equal(i, ids[coff[c]:coff[c + 1]])
+
+
+def test_c2_full_size_matches_oracle():
+    w = W.CONFIGS["C2"]
+    dw = DeviceWorkload(w)
+    q = W.queries(w)
+    say("C2: search nq=32 nprobe=32 k=10")
+    got = gpu_search(dw.index, q, w.nprobe, w.k)
+    res = check_large(dw, q, w.nprobe, w.k, got)
+    say(f"C2 ok: {res}")
+    _check_assignment_sample(dw)
+    _check_readback(dw, [0, 1234, w.nlist - 1])
+    st = dw.index.last_search_stats()
+    assert st.pairs == w.nq * w.nprobe and st.scan_bytes == st.scanned_vectors * w.d * 4
+    dw.index.close()
+
+
+@pytest.fixture(scope="module")
+def c3():
+    dw = DeviceWorkload(W.CONFIGS["C3"])
+    yield dw
+    dw.index.close()
+
+
+def test_c3_full_size_matches_oracle(c3):
+    w = c3.w
+    q = W.queries(w)
+    say("C3: search nq=64 nprobe=64 k=20")
+    got = gpu_search(c3.index, q, w.nprobe, w.k)
+    res = check_large(c3, q, w.nprobe, w.k, got)
+    say(f"C3 ok: {res}")
+    _check_assignment_sample(c3)
+    _check_readback(c3, [5, 9000])
+
+
+def test_c4_offloaded_placement_matches_oracle_and_c3(c3):
+    """Same index and queries as C3 (its first 8), with only the 25 % longest lists
+    (by count, ranked by length then list number) resident in HBM."""
+    w = W.CONFIGS["C4"]
+    q = W.queries(w)
+    assert np.array_equal(q, W.queries(W.CONFIGS["C3"])[:w.nq])
+    say("C4: reference search with everything resident")
+    ref = gpu_search(c3.index, q, w.nprobe, w.k)
+    lens = np.diff(c3.off)
+    order = np.lexsort((np.arange(w.nlist), -lens))
+    keep = order[: int(w.nlist * w.resident_list_frac)]
+    nblk = (lens + 63) // 64
+    budget = int(nblk[keep].sum()) * 64 * w.d * 2
+    say(f"C4: device budget {budget / 2**30:.2f} GiB -> moving lists to pinned host memory")
+    c3.index.set_device_budget(budget)
+    info = c3.index.info()
+    assert info.resident_lists == len(keep) and info.device_list_bytes == budget
+    say("C4: offloaded search nq=8 nprobe=64 k=20")
+    got = gpu_search(c3.index, q, w.nprobe, w.k)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    res = check_large(c3, q, w.nprobe, w.k, got)
+    st = c3.index.last_search_stats()
+    assert st.scan_bytes_streamed > 0 and st.scan_bytes_resident + st.scan_bytes_streamed == st.scan_bytes
+    say(f"C4 ok: {res}; streamed {st.scan_bytes_streamed / 1e6:.0f} MB, resident {st.scan_bytes_resident / 1e6:.0f} MB")
+    _check_readback(c3, [int(order[0]), int(order[-1])])
+    # a second batch through the same staging buffers
+    q2 = W.queries(W.CONFIGS["C3"], batch=1)[:w.nq]
+    got2 = gpu_search(c3.index, q2, w.nprobe, w.k)
+    check_large(c3, q2, w.nprobe, w.k, got2)
+    say("C4: back to fully resident")
+    c3.index.set_device_budget(2**62)
+    got3 = gpu_search(c3.index, q, w.nprobe, w.k)
+    assert np.array_equal(got3[0], ref[0]) and np.array_equal(got3[1], ref[1])
+
+
+def test_c5_full_size_sampled_rows_match_oracle():
+    w = W.CONFIGS["C5"]
+    dw = DeviceWorkload(w, groups_per_chunk=32)
+    q = W.queries(w)
+    say("C5: search nq=128 nprobe=128 k=100")
+    got = gpu_search(dw.index, q, w.nprobe, w.k)
+    rows = [0, 17, 63, 64, 101, 127]
+    res = check_large(dw, q, w.nprobe, w.k, got, rows=rows)
+    say(f"C5 ok on rows {rows}: {res}")
+    _check_assignment_sample(dw, nsample_lists=8)
+    _check_readback(dw, [w.nlist - 1])
+    info = dw.index.info()
+    assert info.n == w.n and info.index_bytes >= w.n * w.d * 2
+    dw.index.close()
