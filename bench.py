@@ -62,12 +62,14 @@ def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
         CK.check_topk(got_ids[rows], got_scores[rows], oi, os_, k, CK.SCORE_REL[w.storage])
         return t_coarse + t_scan
 
-    pilot = [0, 1]
-    t_pilot = run(pilot)
-    per_query = t_pilot / len(pilot)
-    n = int(max(2, min(q.shape[0], target_seconds / max(per_query, 1e-6))))
+    # the oracle spreads queries over its threads, so the pilot uses one query per thread
+    threads = O.threads()
+    npilot = min(q.shape[0], threads)
+    t_pilot = run(list(range(npilot)))
+    waves = max(1, int(target_seconds / max(t_pilot, 1e-6)))
+    n = min(q.shape[0], npilot * waves)
     rows = list(range(n))
-    t = run(rows) if n > len(pilot) else t_pilot
+    t = run(rows) if n > npilot else t_pilot
     return {"value": n / t, "unit": "queries/s", "cores": O.threads(), "kind": "oracle",
             "sample": f"first {n} of the {q.shape[0]} queries of batch 0 (fp64 coarse + probe "
                       f"selection + exact scan of their probed lists + sort), search only, "
@@ -85,6 +87,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 skips the CPU baseline")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--n", type=int, default=0, help="override the number of vectors (experiments only)")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also launch the library's plain copy kernel over this many MiB (reference "
+                         "point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -119,6 +124,15 @@ def main():
     q_dev = [torch.from_numpy(q).cuda() for q in q_host]
     out_ids = torch.empty((w.nq, w.k), dtype=torch.int64, device="cuda")
     out_scores = torch.empty((w.nq, w.k), dtype=torch.float32, device="cuda")
+
+    if args.calibrate_copy_mib:
+        nbytes = args.calibrate_copy_mib << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            idx.debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     idx.set_timing(True)
     stats = []

@@ -180,6 +180,11 @@ enum {
 int ivf_set_timing(ivf_index *idx, int enable);
 int ivf_get_stage_ms(ivf_index *idx, int back, float *ms /* [IVF_NUM_STAGES] host */);
 
+/* A plain copy kernel over `bytes` bytes (multiple of 16) of DEVICE memory, enqueued on
+   `stream`: reads `bytes`, writes `bytes`, nothing else.  It is the reference point of
+   known size against which hardware byte counters of the search kernels are scaled. */
+int ivf_debug_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
 /* Tuning knobs for experiments (launch shape of the scan kernel etc.); unknown names
    return IVF_ERR_INVALID.  Defaults are the tuned values. */
 int ivf_set_option(ivf_index *idx, const char *name, int64_t value);

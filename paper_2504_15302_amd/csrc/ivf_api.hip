@@ -999,6 +999,17 @@ int ivf_get_stage_ms(ivf_index* x, int back, float* ms) {
     return 0;
 }
 
+int ivf_debug_copy(void* dst, const void* src, int64_t bytes, void* stream) {
+    if (!dst || !src || bytes < 0 || bytes % 16 != 0) return fail(IVF_ERR_INVALID, "dst/src NULL or bytes not a multiple of 16");
+    if (bytes == 0) return 0;
+    const size_t n = (size_t)bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(k_copy_u4, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<u4*>(dst), static_cast<const u4*>(src), n);
+    HIP_TRY(hipGetLastError());
+    return 0;
+}
+
 int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     if (!x || !name) return fail(IVF_ERR_INVALID, "index or name is NULL");
     std::string n(name);

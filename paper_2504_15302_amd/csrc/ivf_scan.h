@@ -251,6 +251,13 @@ __global__ __launch_bounds__(256) void k_unlayout(const char* __restrict__ block
     }
 }
 
+// Plain streaming copy, 16 bytes per lane and step (counter calibration).
+__global__ __launch_bounds__(256) void k_copy_u4(u4* __restrict__ dst, const u4* __restrict__ src, size_t n) {
+    size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
 __global__ void k_iota_u32(uint32_t* __restrict__ p, size_t n) {
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
     if (i < n) p[i] = (uint32_t)i;

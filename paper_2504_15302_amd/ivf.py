@@ -25,7 +25,7 @@ EXPORTS = (
     "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
-    "ivf_set_option",
+    "ivf_set_option", "ivf_debug_copy",
 )
 
 
@@ -85,6 +85,7 @@ def load_library() -> C.CDLL:
     lib.ivf_set_timing.argtypes = [vp, i32]
     lib.ivf_get_stage_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
     lib.ivf_set_option.argtypes = [vp, C.c_char_p, i64]
+    lib.ivf_debug_copy.argtypes = [vp, vp, i64, vp]
     for name in EXPORTS:
         if name not in ("ivf_index_destroy", "ivf_last_error"):
             getattr(lib, name).restype = C.c_int
@@ -226,6 +227,12 @@ class Index:
         arr = (C.c_float * len(STAGES))()
         _check(self._lib.ivf_get_stage_ms(self._h, back, arr))
         return {name: float(arr[i]) for i, name in enumerate(STAGES)}
+
+    def debug_copy(self, dst, src, stream=None):
+        """Plain device-to-device copy kernel of known size (counter calibration)."""
+        assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+        _check(self._lib.ivf_debug_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(),
+                                        _stream_handle(stream)))
 
     def set_option(self, name: str, value: int):
         _check(self._lib.ivf_set_option(self._h, name.encode(), int(value)))
