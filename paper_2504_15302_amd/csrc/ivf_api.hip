@@ -73,7 +73,8 @@ struct Scratch {
     float* S = nullptr;
     float* tmax = nullptr;
     int32_t* probes = nullptr;
-    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16]
+    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16] | counters (8 x u64)
+    uint32_t* wg_totals = nullptr;
     uint32_t* pair_start = nullptr;
     uint32_t* sblk_start = nullptr;
     uint32_t* item_start = nullptr;
@@ -148,7 +149,7 @@ struct ivf_index {
     bool ev_created = false;
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 8, opt_scan_wgs_per_cu = 2, opt_stage_mb = 64,
+    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_stage_mb = 64,
             opt_nstage = 3;
 };
 
@@ -156,7 +157,7 @@ namespace {
 
 void free_scratch(Scratch& s) {
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
-    dfree(s.sblk_start); dfree(s.item_start); dfree(s.counters); dfree(s.pair_flat);
+    dfree(s.sblk_start); dfree(s.item_start); dfree(s.wg_totals); dfree(s.pair_flat);
     dfree(s.pair_q); dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
     dfree(s.scores); dfree(s.bmax);
     if (s.h_probes) (void)hipHostFree(s.h_probes);
@@ -230,11 +231,12 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
         s.cap_q_ntile = (size_t)nq * ntile;
     }
     if (x->nlist > s.cap_nlist) {
-        if ((rc = dalloc(s.zeroed, 2 * (size_t)x->nlist + 16, s.bytes))) return rc;
+        if ((rc = dalloc(s.zeroed, 2 * (size_t)x->nlist + 16 + 2 * kNumCounters, s.bytes))) return rc;
+        s.counters = reinterpret_cast<unsigned long long*>(s.zeroed + 2 * (size_t)x->nlist + 16);
+        if ((rc = dalloc(s.wg_totals, 3 * (((size_t)x->nlist + kScanThreads - 1) / kScanThreads), s.bytes))) return rc;
         if ((rc = dalloc(s.pair_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.sblk_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.item_start, (size_t)x->nlist, s.bytes))) return rc;
-        if ((rc = dalloc(s.counters, (size_t)kNumCounters, s.bytes))) return rc;
         s.cap_nlist = x->nlist;
         if (!s.h_counters)
             HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&s.h_counters), sizeof(unsigned long long) * kNumCounters));
@@ -800,7 +802,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
 
     mark();   // 0
     {
-        size_t nz = 2 * (size_t)nlist + 16;
+        size_t nz = 2 * (size_t)nlist + 16 + 2 * kNumCounters;
         hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, s.zeroed, nz);
     }
     {
@@ -826,8 +828,14 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
         HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)npairs, hipMemcpyDeviceToHost, st));
         HIP_TRY(hipEventRecord(x->ev_probes, st));
     }
-    hipLaunchKernelGGL(k_list_scan, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr, nlist,
-                       s.pair_start, s.sblk_start, s.item_start, s.counters);
+    {
+        const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
+        hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                           nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
+        if (wgs > 1)
+            hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, nlist, s.wg_totals, s.pair_start,
+                               s.sblk_start, s.item_start);
+    }
     hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
                        s.pair_start, cursor, s.pair_flat);
     hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,

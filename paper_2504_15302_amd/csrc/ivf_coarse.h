@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
     const int n0 = blockIdx.x * kCoarseNT + wave * 32;
     const int n = n0 + col;
     const bool n_ok = n < nlist;
-    const float* crow = C + (size_t)(n_ok ? n : 0) * d;
+    const float* crow = C + (size_t)(n_ok ? n : nlist - 1) * d;
 
     v16f acc[MT];
 #pragma unroll
@@ -43,37 +43,71 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mt][v] = 0.f;
 
-    for (int kb = 0; kb < d; kb += kCoarseKT) {
-        // stage the query tile [MT*32, 32] into LDS
-        __syncthreads();
+    // Software pipeline over k: the centroid operand and the query tile of step i+1 are
+    // loaded into registers while the MFMAs of step i run, so the HBM/L2 latency hides
+    // behind 16*MT matrix instructions per wavefront.
+    // All loads are unconditional (addresses clamped into range, so the loads of a
+    // step issue back to back); rows past nq / nlist produce values that are never
+    // stored, and a k past d (d not a multiple of 32) is zeroed in the centroid operand.
+    auto load_b = [&](v4f (&b)[4], int kb) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int kk = kb + j * 8 + half * 4;
+            b[j] = *reinterpret_cast<const v4f*>(crow + min(kk, d - 4));
+        }
+    };
+    auto mask_b = [&](v4f (&b)[4], int kb) {        // applied when the values are first used
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kb + j * 8 + half * 4 >= d) b[j] = v4f{0.f, 0.f, 0.f, 0.f};
+    };
+    auto load_q = [&](v4f (&qr)[MT], int kb) {
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             int idx = threadIdx.x + i * 256;
             int row = idx >> 3, c4 = idx & 7;
-            int m = m0 + row, kk = kb + c4 * 4;
-            v4f val = {0.f, 0.f, 0.f, 0.f};
-            if (m < nq && kk < d) val = *reinterpret_cast<const v4f*>(Q + (size_t)m * d + kk);
-            *reinterpret_cast<v4f*>(&qs[row * kCoarseLd + c4 * 4]) = val;
+            int m = min(m0 + row, nq - 1), kk = min(kb + c4 * 4, d - 4);
+            qr[i] = *reinterpret_cast<const v4f*>(Q + (size_t)m * d + kk);
         }
-        // centroid operand of this wavefront, straight from memory
-        v4f b[4];
+    };
+    auto read_a = [&](v4f (&a)[MT], int j) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int kk = kb + j * 8 + half * 4;
-            b[j] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (n_ok && kk < d) b[j] = *reinterpret_cast<const v4f*>(crow + kk);
+        for (int mt = 0; mt < MT; ++mt)
+            a[mt] = *reinterpret_cast<const v4f*>(&qs[(mt * 32 + col) * kCoarseLd + j * 8 + half * 4]);
+    };
+    v4f b_cur[4], b_nxt[4], q_reg[MT];
+    load_b(b_cur, 0);
+    mask_b(b_cur, 0);
+    load_q(q_reg, 0);
+    for (int kb = 0; kb < d; kb += kCoarseKT) {
+        __syncthreads();                    // the previous step's LDS reads are done
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            int idx = threadIdx.x + i * 256;
+            int row = idx >> 3, c4 = idx & 7;
+            *reinterpret_cast<v4f*>(&qs[row * kCoarseLd + c4 * 4]) = q_reg[i];
         }
         __syncthreads();
+        const int kn = min(kb + kCoarseKT, d - 4);   // last step: a harmless reload
+        load_b(b_nxt, kn);
+        load_q(q_reg, kn);
+        __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of the MFMAs that hide them
+        v4f a_cur[MT], a_nxt[MT];
+        read_a(a_cur, 0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+            if (j < 3) read_a(a_nxt, j + 1);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                v4f a = *reinterpret_cast<const v4f*>(&qs[(mt * 32 + col) * kCoarseLd + j * 8 + half * 4]);
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[j][s], acc[mt], 0, 0, 0);
-            }
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[mt][s], b_cur[j][s], acc[mt], 0, 0, 0);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a_cur[mt] = a_nxt[mt];
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b_cur[j] = b_nxt[j];
+        mask_b(b_cur, kb + kCoarseKT);
     }
 
     // accumulator element v of a lane is row 8*(v/4) + 4*half + v%4, column `col`

@@ -8,7 +8,8 @@ namespace ivf {
 
 constexpr int kLanes = 64;        // vectors per storage block = wavefront width
 constexpr int kQB = 4;            // queries that share one read of a block
-constexpr int kSelThreads = 256;  // workgroup size of the selection kernels
+constexpr int kSelThreads = 1024; // workgroup size of the selection kernels (16 wavefronts:
+                                  // the selection is latency-bound, it wants loads in flight)
 constexpr int kChunk = 2048;      // keys sorted at a time by the streaming top-k
 constexpr int kMaxK = 1024;       // largest k / nprobe
 constexpr int kCoarseTile = 32;   // centroids per coarse tile maximum
@@ -84,15 +85,17 @@ __device__ inline void topk_reset(TopK& t, int k) {
     __syncthreads();
 }
 
-// Merges the t.count keys waiting in buf into top.  Uniform call.
-template <int T>
-__device__ inline void topk_flush(TopK& t) {
+// Merges the t.count keys waiting in buf into top.  Uniform call.  `finalize` maps a
+// waiting key to its final form (e.g. replaces a handle in the low half by the
+// tie-break rank) and runs once per key, all keys in parallel.
+template <int T, class F>
+__device__ inline void topk_flush(TopK& t, F finalize) {
     __syncthreads();
     const int m = t.count, kp = t.kp;
     if (m == 0) return;
     int n = kp;
     while (n < m) n <<= 1;
-    for (int i = m + threadIdx.x; i < n; i += T) t.buf[i] = 0;
+    for (int i = threadIdx.x; i < n; i += T) t.buf[i] = i < m ? finalize(t.buf[i]) : 0;
     bitonic_sort_desc<T>(t.buf, n);
     for (int i = threadIdx.x; i < kp; i += T) {
         uint64_t a = t.top[i], b = t.buf[kp - 1 - i];

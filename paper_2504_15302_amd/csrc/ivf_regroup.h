@@ -17,7 +17,7 @@ __global__ void k_zero_i32(int* __restrict__ p, size_t n) {
     if (i < n) p[i] = 0;
 }
 
-enum {                 // 64-bit counters written by k_list_scan
+enum {                 // 64-bit counters accumulated by k_list_partial (zero on entry)
     kCntPairs = 0,
     kCntScoreBlocks = 1,
     kCntItems = 2,
@@ -29,65 +29,106 @@ enum {                 // 64-bit counters written by k_list_scan
 
 constexpr int kScanThreads = 1024;
 
-// Single workgroup: exclusive prefix sums over the lists.
-__global__ __launch_bounds__(kScanThreads) void k_list_scan(
+// Exclusive prefix sums over the lists, two passes: each workgroup scans its 1024
+// lists (one list per thread, coalesced) and publishes its totals; the second pass adds
+// the totals of the workgroups before it.
+__global__ __launch_bounds__(kScanThreads) void k_list_partial(
     const int* __restrict__ hist, const int32_t* __restrict__ nblk, const int32_t* __restrict__ len,
     const void* const* __restrict__ list_ptr, int nlist, uint32_t* __restrict__ pair_start,
     uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start,
-    unsigned long long* __restrict__ counters) {
-    __shared__ unsigned long long part[kScanThreads][3];
+    uint32_t* __restrict__ wg_totals, unsigned long long* __restrict__ counters) {
+    __shared__ uint32_t wsum[kScanThreads / 64][3];
     __shared__ unsigned long long extra[3];
-    const int t = threadIdx.x;
-    const int per = (nlist + kScanThreads - 1) / kScanThreads;
-    const int l0 = min(nlist, t * per), l1 = min(nlist, l0 + per);
-    unsigned long long a = 0, b = 0, c = 0, uniq = 0, vec = 0, vres = 0;
-    for (int l = l0; l < l1; ++l) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int l = blockIdx.x * kScanThreads + t;
+    uint32_t v[3] = {0, 0, 0};
+    unsigned long long uniq = 0, vec = 0, vres = 0;
+    if (l < nlist) {
         unsigned cnt = (unsigned)hist[l];
         if (cnt) {
             unsigned nb = (unsigned)nblk[l];
             bool res = list_ptr[l] != nullptr;
-            a += cnt;
-            b += (unsigned long long)cnt * nb;
-            if (res) c += (unsigned long long)nb * ((cnt + kQB - 1) / kQB);
-            uniq += 1;
-            vec += (unsigned)len[l];
-            if (res) vres += (unsigned)len[l];
+            v[0] = cnt;
+            v[1] = cnt * nb;
+            v[2] = res ? nb * ((cnt + kQB - 1) / kQB) : 0;
+            uniq = 1;
+            vec = (unsigned)len[l];
+            vres = res ? vec : 0;
         }
     }
-    part[t][0] = a; part[t][1] = b; part[t][2] = c;
     if (t == 0) extra[0] = extra[1] = extra[2] = 0;
-    __syncthreads();
-    atomicAdd(&extra[0], uniq);
-    atomicAdd(&extra[1], vec);
-    atomicAdd(&extra[2], vres);
-    // inclusive Hillis-Steele scan over the per-thread sums
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        unsigned long long x0 = 0, x1 = 0, x2 = 0;
-        if (t >= off) { x0 = part[t - off][0]; x1 = part[t - off][1]; x2 = part[t - off][2]; }
-        __syncthreads();
-        part[t][0] += x0; part[t][1] += x1; part[t][2] += x2;
-        __syncthreads();
-    }
-    unsigned long long ea = part[t][0] - a, eb = part[t][1] - b, ec = part[t][2] - c;
-    for (int l = l0; l < l1; ++l) {
-        pair_start[l] = (uint32_t)ea;
-        sblk_start[l] = (uint32_t)eb;
-        item_start[l] = (uint32_t)ec;
-        unsigned cnt = (unsigned)hist[l];
-        if (cnt) {
-            unsigned nb = (unsigned)nblk[l];
-            ea += cnt;
-            eb += (unsigned long long)cnt * nb;
-            if (list_ptr[l] != nullptr) ec += (unsigned long long)nb * ((cnt + kQB - 1) / kQB);
+    uint32_t inc[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {           // inclusive scan inside the wavefront
+        uint32_t x = v[c];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            uint32_t y = __shfl_up(x, o);
+            if (lane >= o) x += y;
         }
+        inc[c] = x;
+        if (lane == 63) wsum[wave][c] = x;
     }
-    if (t == kScanThreads - 1) {
-        counters[kCntPairs] = part[t][0];
-        counters[kCntScoreBlocks] = part[t][1];
-        counters[kCntItems] = part[t][2];
-        counters[kCntUnique] = extra[0];
-        counters[kCntVectors] = extra[1];
-        counters[kCntVectorsResident] = extra[2];
+    __syncthreads();
+    if (uniq) {
+        atomicAdd(&extra[0], uniq);
+        atomicAdd(&extra[1], vec);
+        atomicAdd(&extra[2], vres);
+    }
+    uint32_t base[3] = {0, 0, 0}, total[3] = {0, 0, 0};
+    for (int w = 0; w < kScanThreads / 64; ++w)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            uint32_t x = wsum[w][c];
+            if (w < wave) base[c] += x;
+            total[c] += x;
+        }
+    if (l < nlist) {
+        pair_start[l] = base[0] + inc[0] - v[0];
+        sblk_start[l] = base[1] + inc[1] - v[1];
+        item_start[l] = base[2] + inc[2] - v[2];
+    }
+    __syncthreads();
+    if (t == 0) {
+#pragma unroll
+        for (int c = 0; c < 3; ++c) wg_totals[blockIdx.x * 3 + c] = total[c];
+        atomicAdd(&counters[kCntPairs], (unsigned long long)total[0]);
+        atomicAdd(&counters[kCntScoreBlocks], (unsigned long long)total[1]);
+        atomicAdd(&counters[kCntItems], (unsigned long long)total[2]);
+        atomicAdd(&counters[kCntUnique], extra[0]);
+        atomicAdd(&counters[kCntVectors], extra[1]);
+        atomicAdd(&counters[kCntVectorsResident], extra[2]);
+    }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_list_finish(
+    int nlist, const uint32_t* __restrict__ wg_totals, uint32_t* __restrict__ pair_start,
+    uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start) {
+    __shared__ uint32_t red[kScanThreads / 64][3];
+    __shared__ uint32_t base[3];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    uint32_t s[3] = {0, 0, 0};
+    for (int w = t; w < (int)blockIdx.x; w += kScanThreads)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) s[c] += wg_totals[w * 3 + c];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s[c] += __shfl_xor(s[c], o);
+        if (lane == 0) red[wave][c] = s[c];
+    }
+    __syncthreads();
+    if (t < 3) {
+        uint32_t x = 0;
+        for (int w = 0; w < kScanThreads / 64; ++w) x += red[w][t];
+        base[t] = x;
+    }
+    __syncthreads();
+    const int l = blockIdx.x * kScanThreads + t;
+    if (l < nlist && blockIdx.x > 0) {
+        pair_start[l] += base[0];
+        sblk_start[l] += base[1];
+        item_start[l] += base[2];
     }
 }
 

@@ -2,9 +2,10 @@
 // query and for the k best candidates among the scores of its probed lists.
 //
 // Values come in fixed-width blocks with a precomputed block maximum.  Level 1 finds
-// the k-th largest block maximum M: at least k values are >= M, so every member of
-// the top-k is >= M and lives in a block whose maximum is >= M.  Level 2 visits only
-// those blocks, keeps the values >= M and sorts them.  Both levels run on a streaming
+// the k-th largest block maximum M (a 32-step search on the order-preserving bits, no
+// sorting): at least k values are >= M, so every member of the top-k is >= M and lives
+// in a block whose maximum is >= M.  Level 2 visits only those blocks, keeps the values
+// >= M (a few more than k unless scores tie massively) and sorts them with a streaming
 // top-k in LDS, so any number of blocks and any number of ties is handled exactly.
 // Keys are (order-preserving score bits, tie-break) and are unique per query, which
 // makes the outcome independent of the order in which keys arrive.
@@ -13,11 +14,14 @@
 
 namespace ivf {
 
+constexpr int kOrdCache = 2 * kChunk;   // block maxima kept in LDS for the threshold search
+                                        // (they borrow the top-k chunk buffer, idle in level 1)
+
 struct SelectShared {
     TopK tk;
     int qual[kChunk];   // blocks that pass level 1
     int nqual;
-    uint32_t thr;
+    int wcount[2][kSelThreads / 64];
 };
 
 // Src must provide:
@@ -35,47 +39,75 @@ __device__ inline void two_level_select(SelectShared& sh, const Src& src, int k)
     constexpr int kWaves = T / 64;
     constexpr int kPerWave = 64 / Src::kWidth;   // blocks a wavefront visits at once
 
-    // level 1: k-th largest block maximum
-    topk_reset<T>(sh.tk, k);
-    for (int base = 0; base < nb; base += kChunk) {
-        int m = min(kChunk, nb - base);
-        for (int i = threadIdx.x; i < m; i += T)
-            sh.tk.buf[i] = ((uint64_t)src.block_max_ord(base + i) << 32) | (uint32_t)(~(uint32_t)(base + i));
-        if (threadIdx.x == 0) sh.tk.count = m;
-        topk_flush<T>(sh.tk);
-    }
-    if (threadIdx.x == 0) sh.thr = (nb >= k) ? (uint32_t)(sh.tk.top[k - 1] >> 32) : 0u;
+    // level 1: thr = k-th largest block maximum (0 if there are fewer than k blocks),
+    // found bit by bit: the largest v such that at least k block maxima are >= v.
+    uint32_t* ords = reinterpret_cast<uint32_t*>(sh.tk.buf);
+    for (int i = threadIdx.x; i < min(nb, kOrdCache); i += T) ords[i] = src.block_max_ord(i);
     __syncthreads();
-    const uint32_t thr = sh.thr;
+    auto ord_at = [&](int i) -> uint32_t { return i < kOrdCache ? ords[i] : src.block_max_ord(i); };
+    uint32_t thr = 0;
+    if (nb >= k) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = thr | (1u << bit);
+            int c = 0;
+            for (int i0 = 0; i0 < nb; i0 += T) {        // uniform trip count: ballots stay whole
+                int i = i0 + threadIdx.x;
+                bool ge = i < nb && ord_at(i) >= cand;
+                c += __popcll(__ballot(ge));
+            }
+            const int slot = bit & 1;
+            if (lane == 0) sh.wcount[slot][wave] = c;
+            __syncthreads();
+            int total = 0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) total += sh.wcount[slot][w];
+            if (total >= k) thr = cand;
+        }
+    }
+    __syncthreads();     // the cached maxima are dead from here on: buf goes back to the top-k
 
-    // level 2: values >= thr from blocks whose maximum is >= thr
+    // level 2: values >= thr from blocks whose maximum is >= thr.  Survivors wait in
+    // buf as (order bits, handle); their tie-breaks are looked up all at once at flush
+    // time, so the dependent memory reads of a round overlap instead of queueing.
+    auto finalize = [&](uint64_t key) -> uint64_t {
+        return (key & 0xffffffff00000000ull) | src.tiebreak((uint32_t)key);
+    };
     topk_reset<T>(sh.tk, k);
     for (int base = 0; base < nb; base += kChunk) {
         int m = min(kChunk, nb - base);
         if (threadIdx.x == 0) sh.nqual = 0;
         __syncthreads();
-        for (int i = threadIdx.x; i < m; i += T)
-            if (src.block_max_ord(base + i) >= thr) sh.qual[atomicAdd(&sh.nqual, 1)] = base + i;
+        for (int i = threadIdx.x; i < m; i += T) {
+            // the cached maxima are still intact while nothing has been appended
+            uint32_t o = base == 0 ? ord_at(i) : src.block_max_ord(base + i);
+            if (o >= thr) sh.qual[atomicAdd(&sh.nqual, 1)] = base + i;
+        }
         __syncthreads();
         const int nqual = sh.nqual;
         // rounds of at most 1024 appended keys, so buf (2048) cannot overflow
-        constexpr int kRound = 1024 / 64 * kPerWave;    // blocks per round
+        constexpr int kRound = 1024 / 64 * kPerWave;         // blocks per round
+        constexpr int kIter = (kRound + kWaves * kPerWave - 1) / (kWaves * kPerWave);
         for (int r0 = 0; r0 < nqual; r0 += kRound) {
-            if (sh.tk.count > kChunk - 1024) topk_flush<T>(sh.tk);   // uniform: count read after a barrier
-            for (int r = r0 + wave * kPerWave; r < min(nqual, r0 + kRound); r += kWaves * kPerWave) {
-                int sub = lane / Src::kWidth;
-                int idx = r + sub;
-                bool ok = idx < nqual;
-                uint32_t ord = 0, handle = 0;
-                if (ok) ok = src.value(sh.qual[idx], lane % Src::kWidth, ord, handle) && ord >= thr;
-                uint64_t key = 0;
-                if (ok) key = ((uint64_t)ord << 32) | src.tiebreak(handle);
-                topk_append(sh.tk, ok, key);
+            if (sh.tk.count > kChunk - 1024) topk_flush<T>(sh.tk, finalize);   // uniform: count read after a barrier
+            uint32_t ordv[kIter], hv[kIter];
+            bool okv[kIter];
+#pragma unroll
+            for (int it = 0; it < kIter; ++it) {
+                int slot = (it * kWaves + wave) * kPerWave + lane / Src::kWidth;
+                int idx = r0 + slot;
+                okv[it] = slot < kRound && idx < nqual;
+                ordv[it] = 0; hv[it] = 0;
+                if (okv[it]) okv[it] = src.value(sh.qual[idx], lane % Src::kWidth, ordv[it], hv[it]);
+            }
+#pragma unroll
+            for (int it = 0; it < kIter; ++it) {
+                bool ok = okv[it] && ordv[it] >= thr;
+                topk_append(sh.tk, ok, ((uint64_t)ordv[it] << 32) | hv[it]);
             }
             __syncthreads();
         }
     }
-    topk_flush<T>(sh.tk);
+    topk_flush<T>(sh.tk, finalize);
 }
 
 // ---------------------------------------------------------------- probe selection
@@ -182,9 +214,21 @@ __global__ __launch_bounds__(kSelThreads) void k_final_select(
         pre[j + 1] = nb;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {       // nprobe <= 1024: a serial prefix is cheap next to the rest
-        pre[0] = 0;
-        for (int j = 0; j < nprobe; ++j) pre[j + 1] += pre[j];
+    if (threadIdx.x < 64) {       // prefix sums of the block counts by the first wavefront
+        const int lane = threadIdx.x;
+        int carry = 0;
+        for (int j0 = 0; j0 < nprobe; j0 += 64) {
+            int j = j0 + lane;
+            int x = j < nprobe ? pre[j + 1] : 0;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                int y = __shfl_up(x, o);
+                if (lane >= o) x += y;
+            }
+            if (j < nprobe) pre[j + 1] = carry + x;
+            carry += __shfl(x, 63);
+        }
+        if (lane == 0) pre[0] = 0;
     }
     __syncthreads();
     ScanSrc src{pre, sb, plen, ppos0, nprobe, bmax, scores, rank_of_pos};

@@ -224,7 +224,7 @@ def test_scan_launch_options_agree(c1):
                 assert np.allclose(got[1], ref[1], rtol=1e-6)
     finally:
         idx.set_option("scan_mode", 0)
-        idx.set_option("scan_unroll", 8)
+        idx.set_option("scan_unroll", 16)
 
 
 def test_error_paths_on_the_gpu(c1):
