@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel over this many MiB (reference "
                          "point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--read-ceiling-gib", type=int, default=24,
+                    help="size of the plain streaming-read measurement (0 skips it)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); "
@@ -133,6 +135,27 @@ def main():
             idx.debug_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+
+    read_ceiling = None
+    if args.read_ceiling_gib:
+        # plain read kernel with the scan's access pattern: what this machine can deliver
+        nbytes = (args.read_ceiling_gib << 30) // 98304 * 98304
+        try:
+            src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+            sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+            idx.debug_read(src, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                idx.debug_read(src, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            read_ceiling = 5 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            del src, sink
+        except torch.OutOfMemoryError:
+            log("no room for the read-ceiling buffer; skipped")
+        torch.cuda.empty_cache()
 
     idx.set_timing(True)
     stats = []
@@ -192,7 +215,8 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": avg_scan_bytes, "ms_per_launch": avg_scan_ms,
-                     "launches_timed": kept},
+                     "launches_timed": kept,
+                     "plain_read_same_pattern_GBps": read_ceiling},
         "stages_ms": stage_avg,
         "coarse_tflops_fp32": coarse_tflops,
         "index_build_seconds": lw.seconds,

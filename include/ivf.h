@@ -185,6 +185,12 @@ int ivf_get_stage_ms(ivf_index *idx, int back, float *ms /* [IVF_NUM_STAGES] hos
    known size against which hardware byte counters of the search kernels are scaled. */
 int ivf_debug_copy(void *dst, const void *src, int64_t bytes, void *stream);
 
+/* A plain streaming read of `bytes` bytes (multiple of 98304) of DEVICE memory with the
+   scan kernel's access pattern and no arithmetic: its rate is the practical ceiling of
+   the list scan on the machine at hand.  `sink` is a DEVICE word that is not written
+   for ordinary data. */
+int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
+
 /* Tuning knobs for experiments (launch shape of the scan kernel etc.); unknown names
    return IVF_ERR_INVALID.  Defaults are the tuned values. */
 int ivf_set_option(ivf_index *idx, const char *name, int64_t value);

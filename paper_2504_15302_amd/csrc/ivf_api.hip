@@ -73,14 +73,15 @@ struct Scratch {
     float* S = nullptr;
     float* tmax = nullptr;
     int32_t* probes = nullptr;
-    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16] | counters (8 x u64)
+    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16] | counters (8 x u64) | qthr (nq x u64)
+    unsigned long long* qthr = nullptr;   // per query: running lower bounds of its k-th best score
+    size_t cap_zero_q = 0;
     uint32_t* wg_totals = nullptr;
     uint32_t* pair_start = nullptr;
     uint32_t* sblk_start = nullptr;
     uint32_t* item_start = nullptr;
     unsigned long long* counters = nullptr;
     uint32_t* pair_flat = nullptr;
-    uint32_t* pair_q = nullptr;
     uint32_t* pair_of_probe = nullptr;
     ScanItem* items = nullptr;
     ScanItem* stream_items = nullptr;
@@ -140,6 +141,7 @@ struct ivf_index {
     bool done_recorded = false;
     // search state
     Scratch sc;
+    int prune_blocks = 0, prune_j = 0;   // bound kept by the scan for the current search (see k_scan)
     int last_nq = 0, last_nprobe = 0;
     hipStream_t last_stream = nullptr;
     bool last_offload = false;
@@ -149,7 +151,7 @@ struct ivf_index {
     bool ev_created = false;
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_stage_mb = 64,
+    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_stage_mb = 64,
             opt_nstage = 3;
 };
 
@@ -158,7 +160,7 @@ namespace {
 void free_scratch(Scratch& s) {
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
     dfree(s.sblk_start); dfree(s.item_start); dfree(s.wg_totals); dfree(s.pair_flat);
-    dfree(s.pair_q); dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
+    dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
     dfree(s.scores); dfree(s.bmax);
     if (s.h_probes) (void)hipHostFree(s.h_probes);
     if (s.h_items) (void)hipHostFree(s.h_items);
@@ -230,10 +232,15 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
         if ((rc = dalloc(s.tmax, (size_t)nq * ntile, s.bytes))) return rc;
         s.cap_q_ntile = (size_t)nq * ntile;
     }
-    if (x->nlist > s.cap_nlist) {
-        if ((rc = dalloc(s.zeroed, 2 * (size_t)x->nlist + 16 + 2 * kNumCounters, s.bytes))) return rc;
+    if (x->nlist > s.cap_nlist || (size_t)nq > s.cap_zero_q) {
+        const size_t qcap = std::max<size_t>((size_t)nq, s.cap_zero_q);
+        if ((rc = dalloc(s.zeroed, 2 * (size_t)x->nlist + 16 + 2 * kNumCounters + 2 * qcap, s.bytes))) return rc;
         s.counters = reinterpret_cast<unsigned long long*>(s.zeroed + 2 * (size_t)x->nlist + 16);
-        if ((rc = dalloc(s.wg_totals, 3 * (((size_t)x->nlist + kScanThreads - 1) / kScanThreads), s.bytes))) return rc;
+        s.qthr = s.counters + kNumCounters;
+        s.cap_zero_q = qcap;
+    }
+    if (x->nlist > s.cap_nlist) {
+        if ((rc = dalloc(s.wg_totals, kScanVals * (((size_t)x->nlist + kScanThreads - 1) / kScanThreads), s.bytes))) return rc;
         if ((rc = dalloc(s.pair_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.sblk_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.item_start, (size_t)x->nlist, s.bytes))) return rc;
@@ -244,7 +251,6 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
     if (npairs > s.cap_pairs) {
         if ((rc = dalloc(s.probes, npairs, s.bytes))) return rc;
         if ((rc = dalloc(s.pair_flat, npairs, s.bytes))) return rc;
-        if ((rc = dalloc(s.pair_q, npairs, s.bytes))) return rc;
         if ((rc = dalloc(s.pair_of_probe, npairs, s.bytes))) return rc;
         s.cap_pairs = npairs;
     }
@@ -281,32 +287,39 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
     return 0;
 }
 
-template <bool HALF>
-void launch_scan_u(ivf_index* x, int U, dim3 grid, hipStream_t st, const ScanItem* items,
+template <bool HALF, int U, int WAVES>
+void launch_scan_k(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
                    const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
     Scratch& s = x->sc;
     unsigned int* queue = reinterpret_cast<unsigned int*>(s.zeroed + 2 * (size_t)x->nlist);
-    switch (U) {
-        case 4:
-            hipLaunchKernelGGL((k_scan<HALF, 4>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
-                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
-            break;
-        case 16:
-            hipLaunchKernelGGL((k_scan<HALF, 16>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
-                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
-            break;
-        default:
-            hipLaunchKernelGGL((k_scan<HALF, 8>), grid, dim3(kScanWaves * 64), 0, st, items, n_dev, n_host, Q,
-                               s.pair_q, x->d, s.scores, s.bmax, mode, queue);
+    dim3 grid = mode == 0 ? dim3((unsigned)((work_items + WAVES - 1) / WAVES))
+                          : dim3((unsigned)(x->cus * std::max<int64_t>(1, x->opt_scan_wgs_per_cu)));
+    hipLaunchKernelGGL((k_scan<HALF, U, WAVES>), grid, dim3(WAVES * 64), 0, st, items, n_dev, n_host, Q, x->d,
+                       s.scores, s.bmax, mode, queue, s.qthr, x->prune_blocks, x->prune_j);
+}
+
+template <bool HALF, int U>
+void launch_scan_w(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
+                   const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
+    switch ((int)x->opt_scan_waves) {
+        case 1: launch_scan_k<HALF, U, 1>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        case 2: launch_scan_k<HALF, U, 2>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        case 8: launch_scan_k<HALF, U, 8>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        default: launch_scan_k<HALF, U, 4>(x, work_items, st, items, n_dev, n_host, Q, mode);
     }
 }
 
-void launch_scan(ivf_index* x, dim3 grid, hipStream_t st, const ScanItem* items,
+// work_items: number of items (mode 0: an upper bound is enough, excess wavefronts exit)
+void launch_scan(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
                  const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
-    if (x->dtype == IVF_FP16)
-        launch_scan_u<true>(x, (int)x->opt_scan_unroll, grid, st, items, n_dev, n_host, Q, mode);
-    else
-        launch_scan_u<false>(x, (int)x->opt_scan_unroll, grid, st, items, n_dev, n_host, Q, mode);
+    const int U = (int)x->opt_scan_unroll;
+    if (x->dtype == IVF_FP16) {
+        if (U == 8) launch_scan_w<true, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        else launch_scan_w<true, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+    } else {
+        if (U == 8) launch_scan_w<false, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        else launch_scan_w<false, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+    }
 }
 
 int ensure_staging(ivf_index* x) {
@@ -345,7 +358,7 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
     stt = ivf_search_stats();
     stt.pairs = (int64_t)npairs;
 
-    struct HostList { int32_t l; uint32_t cnt, ps, sb; };
+    struct HostList { int32_t l; uint32_t cnt, ps, sb; size_t first; };   // first: index into pl
     std::vector<HostList> hl;
     uint32_t ps = 0, sb = 0;
     for (size_t i = 0; i < npairs;) {
@@ -362,7 +375,7 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
             stt.scan_items += (int64_t)x->nblk[l] * ((cnt + kQB - 1) / kQB);
         } else {
             stt.scan_bytes_streamed += bytes;
-            if (x->nblk[l] > 0) hl.push_back({l, cnt, ps, sb});
+            if (x->nblk[l] > 0) hl.push_back({l, cnt, ps, sb, i});
         }
         ps += cnt;
         sb += cnt * (uint32_t)x->nblk[l];
@@ -412,9 +425,11 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
                     it.data = x->stage[slot] + loff + (size_t)b * x->block_bytes;
                     it.sblk = h.sb + g * kQB * nb + b;
                     it.nblk = nb;
-                    it.pair0 = h.ps + g * kQB;
-                    it.nq = std::min<uint32_t>(kQB, h.cnt - g * kQB);
-                    it.nvalid = std::min<uint32_t>(64u, (uint32_t)x->len[h.l] - b * 64u);
+                    const uint32_t nqg = std::min<uint32_t>(kQB, h.cnt - g * kQB);
+                    for (uint32_t jq = 0; jq < (uint32_t)kQB; ++jq)
+                        it.q[jq] = (uint16_t)(pl[h.first + g * kQB + std::min(jq, nqg - 1)].second / (uint32_t)nprobe);
+                    it.nq = (uint16_t)nqg;
+                    it.nvalid = (uint16_t)std::min<uint32_t>(64u, (uint32_t)x->len[h.l] - b * 64u);
                     it.pad = 0;
                     s.h_items[item_off++] = it;
                 }
@@ -425,8 +440,7 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
                                nitems * sizeof(ScanItem), hipMemcpyHostToDevice, x->side));
         HIP_TRY(hipEventRecord(x->stage_ready[slot], x->side));
         HIP_TRY(hipStreamWaitEvent(st, x->stage_ready[slot], 0));
-        dim3 grid((unsigned)((nitems + kScanWaves - 1) / kScanWaves));
-        launch_scan(x, grid, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q, 0);
+        launch_scan(x, nitems, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q, 0);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(x->stage_free[slot], st));
         x->stage_used[slot] = true;
@@ -795,6 +809,14 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     const int nlist = (int)x->nlist;
     const int ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
     const int npairs = (int)(nq * nprobe);
+    // Running lower bound of each query's k-th best score, kept by the scan so that it
+    // can skip storing blocks that cannot matter: from one block's k-th largest value
+    // (k <= 64) or from the two best blocks' ceil(k/2)-th largest (k <= 128).
+    // Small plans run as one wave of work items, where nothing has a bound to prune by yet.
+    const bool small_plan = x->opt_scan_prune != 2 && block_bound(x, nq, nprobe) < 32768;
+    if (!x->opt_scan_prune || k > 128 || small_plan) { x->prune_blocks = 0; x->prune_j = 0; }
+    else if (k <= 64) { x->prune_blocks = 1; x->prune_j = k; }
+    else { x->prune_blocks = 2; x->prune_j = (k + 1) / 2; }
     const bool tm = x->timing;
     hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
     int evi = 0;
@@ -802,7 +824,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
 
     mark();   // 0
     {
-        size_t nz = 2 * (size_t)nlist + 16 + 2 * kNumCounters;
+        size_t nz = 2 * (size_t)nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq;
         hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, s.zeroed, nz);
     }
     {
@@ -832,26 +854,19 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
         const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
         hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
                            nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
-        if (wgs > 1)
-            hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, nlist, s.wg_totals, s.pair_start,
-                               s.sblk_start, s.item_start);
+        hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, hist, nlist, (int)wgs, s.wg_totals,
+                           s.pair_start, s.sblk_start, s.item_start);
     }
     hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
                        s.pair_start, cursor, s.pair_flat);
     hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
                        x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
-                       s.pair_flat, s.pair_q, s.pair_of_probe, s.items);
+                       s.pair_flat, s.pair_of_probe, s.items);
     mark();   // 3
     if (x->resident_lists > 0) {
         const int mode = (int)x->opt_scan_mode;
-        dim3 grid;
-        if (mode == 0) {
-            int64_t bound = std::max<int64_t>(1, block_bound(x, nq, nprobe));
-            grid = dim3((unsigned)((bound + kScanWaves - 1) / kScanWaves));
-        } else {
-            grid = dim3((unsigned)(x->cus * std::max<int64_t>(1, x->opt_scan_wgs_per_cu)));
-        }
-        launch_scan(x, grid, st, s.items, s.counters + kCntItems, 0, queries, mode);
+        const int64_t bound = std::max<int64_t>(1, block_bound(x, nq, nprobe));
+        launch_scan(x, (size_t)bound, st, s.items, s.counters + kCntItems, 0, queries, mode);
     }
     mark();   // 4
     HIP_TRY(hipGetLastError());
@@ -862,7 +877,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
     hipLaunchKernelGGL(k_final_select, dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.probes, s.pair_of_probe,
                        s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, nprobe, k,
-                       out_ids, out_scores);
+                       x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
     mark();   // 6
     HIP_TRY(hipGetLastError());
     if (offload) {
@@ -1018,12 +1033,25 @@ int ivf_debug_copy(void* dst, const void* src, int64_t bytes, void* stream) {
     return 0;
 }
 
+int ivf_debug_read(const void* src, int64_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes < 0 || bytes % 98304 != 0)
+        return fail(IVF_ERR_INVALID, "src/sink NULL or bytes not a multiple of 98304");
+    if (bytes == 0) return 0;
+    const size_t ntiles = (size_t)bytes / 98304;
+    hipLaunchKernelGGL(k_read_tiles, dim3((unsigned)((ntiles + 3) / 4)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u4*>(src), ntiles, static_cast<unsigned*>(sink));
+    HIP_TRY(hipGetLastError());
+    return 0;
+}
+
 int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     if (!x || !name) return fail(IVF_ERR_INVALID, "index or name is NULL");
     std::string n(name);
     if (n == "scan_mode" && (value == 0 || value == 1)) x->opt_scan_mode = value;
-    else if (n == "scan_unroll" && (value == 4 || value == 8 || value == 16)) x->opt_scan_unroll = value;
+    else if (n == "scan_unroll" && (value == 8 || value == 16)) x->opt_scan_unroll = value;
+    else if (n == "scan_waves" && (value == 1 || value == 2 || value == 4 || value == 8)) x->opt_scan_waves = value;
     else if (n == "scan_wgs_per_cu" && value >= 1 && value <= 16) x->opt_scan_wgs_per_cu = value;
+    else if (n == "scan_prune" && value >= 0 && value <= 2) x->opt_scan_prune = value;   // 2 = also on small plans
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
     else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);

@@ -19,9 +19,9 @@ struct ScanItem {
     const void* data;   // address of the block (HBM list arena or a staging buffer)
     uint32_t sblk;      // score block of the group's first query; query g adds g*nblk
     uint32_t nblk;      // blocks in the list
-    uint32_t pair0;     // first (list, query) pair of the group
-    uint32_t nq;        // queries in the group, 1..kQB
-    uint32_t nvalid;    // valid vectors in the block, 1..64
+    uint16_t q[kQB];    // query rows of the group (entries past nq repeat the last one)
+    uint16_t nq;        // queries in the group, 1..kQB
+    uint16_t nvalid;    // valid vectors in the block, 1..64
     uint32_t pad;
 };
 static_assert(sizeof(ScanItem) == 32, "ScanItem layout");

@@ -28,38 +28,47 @@ enum {                 // 64-bit counters accumulated by k_list_partial (zero on
 };
 
 constexpr int kScanThreads = 1024;
+constexpr int kHistTopShift = 20;                         // hist[l] = probes + (times best probe << 20)
+constexpr int kHistCountMask = (1 << kHistTopShift) - 1;
+constexpr int kScanVals = 4;   // pairs, score blocks, items of "first" lists, items of the other lists
 
 // Exclusive prefix sums over the lists, two passes: each workgroup scans its 1024
 // lists (one list per thread, coalesced) and publishes its totals; the second pass adds
-// the totals of the workgroups before it.
+// the totals of the workgroups before it.  Scan items are numbered in two classes: lists
+// that are some query's best probe come first, so that the scan meets every query's most
+// promising list early and its bound on the k-th best score is tight almost from the start.
 __global__ __launch_bounds__(kScanThreads) void k_list_partial(
     const int* __restrict__ hist, const int32_t* __restrict__ nblk, const int32_t* __restrict__ len,
     const void* const* __restrict__ list_ptr, int nlist, uint32_t* __restrict__ pair_start,
     uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start,
     uint32_t* __restrict__ wg_totals, unsigned long long* __restrict__ counters) {
-    __shared__ uint32_t wsum[kScanThreads / 64][3];
+    __shared__ uint32_t wsum[kScanThreads / 64][kScanVals];
     __shared__ unsigned long long extra[3];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int l = blockIdx.x * kScanThreads + t;
-    uint32_t v[3] = {0, 0, 0};
+    uint32_t v[kScanVals] = {0, 0, 0, 0};
     unsigned long long uniq = 0, vec = 0, vres = 0;
+    bool first = false;
     if (l < nlist) {
-        unsigned cnt = (unsigned)hist[l];
+        const unsigned h = (unsigned)hist[l];
+        const unsigned cnt = h & kHistCountMask;
         if (cnt) {
             unsigned nb = (unsigned)nblk[l];
             bool res = list_ptr[l] != nullptr;
+            first = (h >> kHistTopShift) != 0;
             v[0] = cnt;
             v[1] = cnt * nb;
-            v[2] = res ? nb * ((cnt + kQB - 1) / kQB) : 0;
+            unsigned items = res ? nb * ((cnt + kQB - 1) / kQB) : 0;
+            v[first ? 2 : 3] = items;
             uniq = 1;
             vec = (unsigned)len[l];
             vres = res ? vec : 0;
         }
     }
     if (t == 0) extra[0] = extra[1] = extra[2] = 0;
-    uint32_t inc[3];
+    uint32_t inc[kScanVals];
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {           // inclusive scan inside the wavefront
+    for (int c = 0; c < kScanVals; ++c) {           // inclusive scan inside the wavefront
         uint32_t x = v[c];
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -75,10 +84,10 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
         atomicAdd(&extra[1], vec);
         atomicAdd(&extra[2], vres);
     }
-    uint32_t base[3] = {0, 0, 0}, total[3] = {0, 0, 0};
+    uint32_t base[kScanVals] = {0, 0, 0, 0}, total[kScanVals] = {0, 0, 0, 0};
     for (int w = 0; w < kScanThreads / 64; ++w)
 #pragma unroll
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < kScanVals; ++c) {
             uint32_t x = wsum[w][c];
             if (w < wave) base[c] += x;
             total[c] += x;
@@ -86,15 +95,15 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
     if (l < nlist) {
         pair_start[l] = base[0] + inc[0] - v[0];
         sblk_start[l] = base[1] + inc[1] - v[1];
-        item_start[l] = base[2] + inc[2] - v[2];
+        item_start[l] = first ? base[2] + inc[2] - v[2] : base[3] + inc[3] - v[3];   // within its class
     }
     __syncthreads();
     if (t == 0) {
 #pragma unroll
-        for (int c = 0; c < 3; ++c) wg_totals[blockIdx.x * 3 + c] = total[c];
+        for (int c = 0; c < kScanVals; ++c) wg_totals[blockIdx.x * kScanVals + c] = total[c];
         atomicAdd(&counters[kCntPairs], (unsigned long long)total[0]);
         atomicAdd(&counters[kCntScoreBlocks], (unsigned long long)total[1]);
-        atomicAdd(&counters[kCntItems], (unsigned long long)total[2]);
+        atomicAdd(&counters[kCntItems], (unsigned long long)total[2] + total[3]);
         atomicAdd(&counters[kCntUnique], extra[0]);
         atomicAdd(&counters[kCntVectors], extra[1]);
         atomicAdd(&counters[kCntVectorsResident], extra[2]);
@@ -102,33 +111,38 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
 }
 
 __global__ __launch_bounds__(kScanThreads) void k_list_finish(
-    int nlist, const uint32_t* __restrict__ wg_totals, uint32_t* __restrict__ pair_start,
-    uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start) {
-    __shared__ uint32_t red[kScanThreads / 64][3];
-    __shared__ uint32_t base[3];
+    const int* __restrict__ hist, int nlist, int nwg, const uint32_t* __restrict__ wg_totals,
+    uint32_t* __restrict__ pair_start, uint32_t* __restrict__ sblk_start,
+    uint32_t* __restrict__ item_start) {
+    __shared__ uint32_t red[kScanThreads / 64][kScanVals + 1];
+    __shared__ uint32_t base[kScanVals + 1];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    uint32_t s[3] = {0, 0, 0};
-    for (int w = t; w < (int)blockIdx.x; w += kScanThreads)
+    uint32_t s[kScanVals + 1] = {0, 0, 0, 0, 0};      // [4] = items of "first" lists, all workgroups
+    for (int w = t; w < nwg; w += kScanThreads) {
+        if (w < (int)blockIdx.x)
 #pragma unroll
-        for (int c = 0; c < 3; ++c) s[c] += wg_totals[w * 3 + c];
+            for (int c = 0; c < kScanVals; ++c) s[c] += wg_totals[w * kScanVals + c];
+        s[kScanVals] += wg_totals[w * kScanVals + 2];
+    }
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c <= kScanVals; ++c) {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) s[c] += __shfl_xor(s[c], o);
         if (lane == 0) red[wave][c] = s[c];
     }
     __syncthreads();
-    if (t < 3) {
+    if (t <= kScanVals) {
         uint32_t x = 0;
         for (int w = 0; w < kScanThreads / 64; ++w) x += red[w][t];
         base[t] = x;
     }
     __syncthreads();
     const int l = blockIdx.x * kScanThreads + t;
-    if (l < nlist && blockIdx.x > 0) {
+    if (l < nlist) {
+        const bool first = ((unsigned)hist[l] >> kHistTopShift) != 0;
         pair_start[l] += base[0];
         sblk_start[l] += base[1];
-        item_start[l] += base[2];
+        item_start[l] += first ? base[2] : base[kScanVals] + base[3];
     }
 }
 
@@ -151,11 +165,10 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
                        const uint32_t* __restrict__ pair_start,
                        const uint32_t* __restrict__ sblk_start,
                        const uint32_t* __restrict__ item_start, uint32_t* __restrict__ pair_flat,
-                       uint32_t* __restrict__ pair_q, uint32_t* __restrict__ pair_of_probe,
-                       ScanItem* __restrict__ items) {
+                       uint32_t* __restrict__ pair_of_probe, ScanItem* __restrict__ items) {
     int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
-    const unsigned cnt = (unsigned)hist[l];
+    const unsigned cnt = (unsigned)hist[l] & kHistCountMask;
     if (!cnt) return;
     const uint32_t ps = pair_start[l];
     uint32_t* seg = pair_flat + ps;
@@ -166,9 +179,7 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
         seg[j + 1] = v;
     }
     for (unsigned i = 0; i < cnt; ++i) {
-        uint32_t f = seg[i];
-        pair_q[ps + i] = f / (uint32_t)nprobe;
-        pair_of_probe[f] = ps + i;
+        pair_of_probe[seg[i]] = ps + i;
     }
     const char* base = static_cast<const char*>(list_ptr[l]);
     if (!base) return;
@@ -183,9 +194,11 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
             it.data = base + (size_t)b * block_bytes;
             it.sblk = sblk_start[l] + g * kQB * nb + b;
             it.nblk = nb;
-            it.pair0 = ps + g * kQB;
-            it.nq = nqg;
-            it.nvalid = min(64u, ln - b * 64u);
+#pragma unroll
+            for (unsigned j = 0; j < kQB; ++j)
+                it.q[j] = (uint16_t)(seg[g * kQB + min(j, nqg - 1)] / (uint32_t)nprobe);
+            it.nq = (uint16_t)nqg;
+            it.nvalid = (uint16_t)min(64u, ln - b * 64u);
             it.pad = 0;
             out[g * nb + b] = it;
         }

@@ -13,9 +13,12 @@
 //     is broadcast with a lane read and enters the FMA as a scalar operand — no LDS,
 //     no dependence on d, one vector register per query and 64 dimensions;
 //   * up to kQB queries that probe the same list share one read of the block;
-//   * scores go to a scratch array (4 bytes per vector and query, ~0.3 % of the bytes
-//     read) together with the maximum of each block of 64, which the final selection
-//     uses to visit only the few blocks that can hold a top-k member.
+//   * the maximum of each block of 64 scores always goes to a scratch array; the 64
+//     scores themselves (4 bytes per vector and query, ~0.3 % of the bytes read — but
+//     measured to cost ~5 % of the read bandwidth when all are stored) are stored only
+//     for blocks whose maximum reaches a running lower bound of the query's k-th best
+//     score.  The final selection visits only blocks at or above the final bound, so it
+//     never reads a block that was skipped.
 #pragma once
 #include "ivf_device.h"
 
@@ -108,9 +111,10 @@ __device__ __forceinline__ void fma_group(const ScanBuf<NQ, UU, E>& b, float (&a
 
 template <bool HALF, int NQ, int U>
 __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __restrict__ Q,
-                                          const uint32_t* __restrict__ pair_q, int d,
-                                          float* __restrict__ scores, float* __restrict__ bmax,
-                                          int lane) {
+                                          int d, float* __restrict__ scores,
+                                          float* __restrict__ bmax, int lane,
+                                          unsigned long long* __restrict__ qthr, int prune_blocks,
+                                          int prune_j) {
     constexpr int E = Store<HALF>::E;
     const int nchunk = d / E;
     const int nq = (int)it.nq;
@@ -122,8 +126,7 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
     const float* qrow[NQ];
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
-        uint32_t qi = pair_q[it.pair0 + (uint32_t)min(g, nq - 1)];
-        qrow[g] = Q + (size_t)qi * d;
+        qrow[g] = Q + (size_t)it.q[g] * d;
     }
     float acc[NQ];
 #pragma unroll
@@ -159,10 +162,46 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
         if (g < nq) {
-            float s = valid ? acc[g] : -INFINITY;
-            uint32_t sb = it.sblk + (uint32_t)g * it.nblk;
-            scores[(size_t)sb * kLanes + lane] = s;
-            float mx = wave_max(s, lane);
+            const float s = valid ? acc[g] : -INFINITY;
+            const uint32_t sb = it.sblk + (uint32_t)g * it.nblk;
+            const float mx = wave_max(s, lane);
+            bool store = true;
+            if (prune_blocks) {
+                // qthr[q] = (best, second best) over blocks of "j-th largest score in the
+                // block"; with one block in play both halves are equal.  The low half is
+                // a lower bound of q's k-th best score: >= k candidates reach it.
+                unsigned long long* slot = qthr + it.q[g];
+                const uint32_t thr = (uint32_t)__atomic_load_n(slot, __ATOMIC_RELAXED);
+                const uint32_t omx = ord_of(mx);
+                if (omx < thr) {
+                    store = false;                 // nothing here can enter the top-k
+                } else {
+                    const uint32_t o = valid ? ord_of(s) : 0u;
+                    uint32_t t = 0;                // j-th largest of the block, bit by bit
+                    for (int bit = 31; bit >= 0; --bit) {
+                        const uint32_t cand = t | (1u << bit);
+                        if (__popcll(__ballot(o >= cand)) >= prune_j) t = cand;
+                    }
+                    if (t > thr && lane == 0) {
+                        if (prune_blocks == 1) {
+                            atomicMax(slot, ((unsigned long long)t << 32) | t);
+                        } else {
+                            unsigned long long old = __atomic_load_n(slot, __ATOMIC_RELAXED);
+                            for (;;) {
+                                const uint32_t hi = (uint32_t)(old >> 32), lo = (uint32_t)old;
+                                unsigned long long nw;
+                                if (t > hi) nw = ((unsigned long long)t << 32) | hi;
+                                else if (t > lo) nw = ((unsigned long long)hi << 32) | t;
+                                else break;
+                                const unsigned long long prev = atomicCAS(slot, old, nw);
+                                if (prev == old) break;
+                                old = prev;
+                            }
+                        }
+                    }
+                }
+            }
+            if (store) __builtin_nontemporal_store(s, scores + (size_t)sb * kLanes + lane);
             if (lane == 0) bmax[sb] = mx;
         }
     }
@@ -170,36 +209,38 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
 
 template <bool HALF, int U>
 __device__ __forceinline__ void scan_dispatch(const ScanItem& it, const float* __restrict__ Q,
-                                              const uint32_t* __restrict__ pair_q, int d,
-                                              float* __restrict__ scores, float* __restrict__ bmax,
-                                              int lane) {
+                                              int d, float* __restrict__ scores,
+                                              float* __restrict__ bmax, int lane,
+                                              unsigned long long* __restrict__ qthr,
+                                              int prune_blocks, int prune_j) {
     if (it.nq == 1)
-        scan_item<HALF, 1, U>(it, Q, pair_q, d, scores, bmax, lane);
+        scan_item<HALF, 1, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     else if (it.nq == 2)
-        scan_item<HALF, 2, U>(it, Q, pair_q, d, scores, bmax, lane);
+        scan_item<HALF, 2, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     else
-        scan_item<HALF, kQB, U>(it, Q, pair_q, d, scores, bmax, lane);
+        scan_item<HALF, kQB, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
 }
 
-constexpr int kScanWaves = 4;   // wavefronts per workgroup of the scan
+constexpr int kScanWaves = 4;   // default wavefronts per workgroup of the scan
 
 // mode 0: one wavefront per item, grid sized by the host's upper bound on the items;
 // mode 1: persistent wavefronts pulling items from an atomic queue (*queue must be 0).
 // The item count comes from device memory (n_items_dev) when the plan was made on the
 // device, else from the host (n_items_host).
-template <bool HALF, int U>
-__global__ __launch_bounds__(kScanWaves * 64) void k_scan(
+template <bool HALF, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_scan(
     const ScanItem* __restrict__ items, const unsigned long long* __restrict__ n_items_dev,
-    uint32_t n_items_host, const float* __restrict__ Q, const uint32_t* __restrict__ pair_q, int d,
-    float* __restrict__ scores, float* __restrict__ bmax, int mode, unsigned int* __restrict__ queue) {
+    uint32_t n_items_host, const float* __restrict__ Q, int d, float* __restrict__ scores,
+    float* __restrict__ bmax, int mode, unsigned int* __restrict__ queue,
+    unsigned long long* __restrict__ qthr, int prune_blocks, int prune_j) {
     const int lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t T = n_items_dev ? (uint32_t)*n_items_dev : n_items_host;
     if (mode == 0) {
-        uint32_t t = blockIdx.x * kScanWaves + wave;
+        uint32_t t = blockIdx.x * WAVES + wave;
         if (t >= T) return;
         ScanItem it = items[t];
-        scan_dispatch<HALF, U>(it, Q, pair_q, d, scores, bmax, lane);
+        scan_dispatch<HALF, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     } else {
         for (;;) {
             // All 64 lanes take part in the atomic (lane 0 adds 1, the others 0) so that
@@ -210,7 +251,7 @@ __global__ __launch_bounds__(kScanWaves * 64) void k_scan(
             t = __builtin_amdgcn_readfirstlane(t);
             if (t >= T) break;           // every wavefront reaches this: the queue only grows
             ScanItem it = items[t];
-            scan_dispatch<HALF, U>(it, Q, pair_q, d, scores, bmax, lane);
+            scan_dispatch<HALF, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
         }
     }
 }
@@ -256,6 +297,37 @@ __global__ __launch_bounds__(256) void k_copy_u4(u4* __restrict__ dst, const u4*
     size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * 256;
     for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// Plain streaming read with the scan's access pattern and nothing else: one wavefront
+// per contiguous 96 KiB tile, two buffers of 8 nontemporal 16-byte loads per lane.  Its
+// rate is the practical ceiling for the scan on this machine.  `sink` is never written
+// unless the data XORs to a magic value (keeps the loads alive).
+__global__ __launch_bounds__(256) void k_read_tiles(const u4* __restrict__ base, size_t ntiles,
+                                                    unsigned* __restrict__ sink) {
+    constexpr int U = 8, kTileU4 = 6144, kSteps = kTileU4 / kLanes;   // 96 loads per lane
+    size_t t = blockIdx.x * (size_t)4 + (threadIdx.x >> 6);
+    if (t >= ntiles) return;
+    const int lane = threadIdx.x & 63;
+    gptr_u4 src = (gptr_u4)(uintptr_t)(base + t * kTileU4) + lane;
+    u4 acc = {0u, 0u, 0u, 0u};
+    u4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(src + u * kLanes);
+    for (int g = 0; g + 2 <= kSteps / U; g += 2) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) b[u] = __builtin_nontemporal_load(src + ((g + 1) * U + u) * kLanes);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= a[u];
+        if (g + 2 < kSteps / U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(src + ((g + 2) * U + u) * kLanes);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= b[u];
+    }
+    unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (r == 0x9e3779b9u) sink[0] = r;
 }
 
 __global__ void k_iota_u32(uint32_t* __restrict__ p, size_t n) {

@@ -30,8 +30,10 @@ struct SelectShared {
 //   bool value(int f, int lane, uint32_t& ord, uint32_t& handle) const   per-lane value
 //   uint32_t tiebreak(uint32_t handle) const       larger = preferred; unique per query
 //   static constexpr int kWidth                    values per block (<= 64)
+// `min_thr`: a lower bound of the k-th best value's order bits that the caller already
+// knows (0 = none); blocks below it are not visited.
 template <class Src>
-__device__ inline void two_level_select(SelectShared& sh, const Src& src, int k) {
+__device__ inline void two_level_select(SelectShared& sh, const Src& src, int k, uint32_t min_thr = 0) {
     constexpr int T = kSelThreads;
     const int nb = src.nblocks();
     const int lane = threadIdx.x & 63;
@@ -64,6 +66,7 @@ __device__ inline void two_level_select(SelectShared& sh, const Src& src, int k)
             if (total >= k) thr = cand;
         }
     }
+    if (min_thr > thr) thr = min_thr;
     __syncthreads();     // the cached maxima are dead from here on: buf goes back to the top-k
 
     // level 2: values >= thr from blocks whose maximum is >= thr.  Survivors wait in
@@ -128,8 +131,10 @@ struct CoarseSrc {
     __device__ uint32_t tiebreak(uint32_t handle) const { return ~handle; }   // smaller list first
 };
 
-// One workgroup per query: probes[q, 0..nprobe) = lists best first; also counts how
-// many queries probe each list (hist must be zero on entry).
+// One workgroup per query: probes[q, 0..nprobe) = lists best first.  Also counts in
+// hist[l] (zero on entry) how many queries probe list l (low 20 bits) and, above bit 20,
+// for how many it is the best probe; of the latter only "non-zero" is used, as an
+// ordering hint for the scan, so wrap-around there is harmless.
 __global__ __launch_bounds__(kSelThreads) void k_probe_select(const float* __restrict__ S,
                                                               const float* __restrict__ tmax,
                                                               int nlist, int ntile, int nprobe,
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_select(const float* __res
         uint32_t lu = ~(uint32_t)key;               // nprobe <= nlist: never an empty key,
         int32_t l = lu < (uint32_t)nlist ? (int32_t)lu : 0;   // but stay in bounds on NaN input
         probes[(size_t)q * nprobe + i] = l;
-        atomicAdd(&hist[l], 1);
+        atomicAdd(&hist[l], 1 + (i == 0 ? (1 << 20) : 0));   // low 20 bits: probes; above: times best probe
     }
 }
 
@@ -197,7 +202,8 @@ __global__ __launch_bounds__(kSelThreads) void k_final_select(
     const uint32_t* __restrict__ pair_start, const uint32_t* __restrict__ sblk_start, ListTable lt,
     const float* __restrict__ bmax, const float* __restrict__ scores,
     const uint32_t* __restrict__ rank_of_pos, const int64_t* __restrict__ id_sorted, int nprobe,
-    int k, int64_t* __restrict__ out_ids, float* __restrict__ out_scores) {
+    int k, const unsigned long long* __restrict__ qthr, int64_t* __restrict__ out_ids,
+    float* __restrict__ out_scores) {
     __shared__ SelectShared sh;
     __shared__ int pre[kMaxK + 1];
     __shared__ uint32_t sb[kMaxK];
@@ -232,7 +238,10 @@ __global__ __launch_bounds__(kSelThreads) void k_final_select(
     }
     __syncthreads();
     ScanSrc src{pre, sb, plen, ppos0, nprobe, bmax, scores, rank_of_pos};
-    two_level_select(sh, src, k);
+    // the scan stored a block's scores only if its maximum reached the bound it kept for
+    // the query; the final bound is at least every bound it used, so visiting only blocks
+    // at or above it never reads a block that was skipped
+    two_level_select(sh, src, k, qthr ? (uint32_t)qthr[q] : 0u);
     for (int i = threadIdx.x; i < k; i += kSelThreads) {
         uint64_t key = sh.tk.top[i];
         int64_t id = -1;

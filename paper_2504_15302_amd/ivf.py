@@ -25,7 +25,7 @@ EXPORTS = (
     "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
-    "ivf_set_option", "ivf_debug_copy",
+    "ivf_set_option", "ivf_debug_copy", "ivf_debug_read",
 )
 
 
@@ -86,6 +86,7 @@ def load_library() -> C.CDLL:
     lib.ivf_get_stage_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
     lib.ivf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.ivf_debug_copy.argtypes = [vp, vp, i64, vp]
+    lib.ivf_debug_read.argtypes = [vp, i64, vp, vp]
     for name in EXPORTS:
         if name not in ("ivf_index_destroy", "ivf_last_error"):
             getattr(lib, name).restype = C.c_int
@@ -232,6 +233,11 @@ class Index:
         """Plain device-to-device copy kernel of known size (counter calibration)."""
         assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
         _check(self._lib.ivf_debug_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(),
+                                        _stream_handle(stream)))
+
+    def debug_read(self, src, sink, stream=None):
+        """Plain streaming-read kernel over `src` (practical HBM read ceiling)."""
+        _check(self._lib.ivf_debug_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
                                         _stream_handle(stream)))
 
     def set_option(self, name: str, value: int):

@@ -214,17 +214,39 @@ def test_scan_launch_options_agree(c1):
     q = W.queries(w, batch=5)
     ref = gpu_search(idx, q, w.nprobe, w.k)
     try:
-        for mode in (0, 1):
-            for unroll in (4, 8, 16):
-                say(f"C1 scan_mode={mode} scan_unroll={unroll}")
-                idx.set_option("scan_mode", mode)
-                idx.set_option("scan_unroll", unroll)
-                got = gpu_search(idx, q, w.nprobe, w.k)
-                assert np.array_equal(got[0], ref[0])
-                assert np.allclose(got[1], ref[1], rtol=1e-6)
+        for mode, unroll, waves in [(0, 8, 4), (0, 16, 4), (1, 8, 4), (1, 16, 4), (0, 16, 1), (0, 16, 2),
+                                    (0, 8, 8), (1, 16, 2)]:
+            say(f"C1 scan_mode={mode} scan_unroll={unroll} scan_waves={waves}")
+            idx.set_option("scan_mode", mode)
+            idx.set_option("scan_unroll", unroll)
+            idx.set_option("scan_waves", waves)
+            got = gpu_search(idx, q, w.nprobe, w.k)
+            assert np.array_equal(got[0], ref[0])
+            assert np.allclose(got[1], ref[1], rtol=1e-6)
     finally:
         idx.set_option("scan_mode", 0)
         idx.set_option("scan_unroll", 16)
+        idx.set_option("scan_waves", 4)
+
+
+@pytest.mark.parametrize("k", [1, 10, 64, 65, 100, 128, 129])
+def test_store_pruning_in_the_scan_does_not_change_results(c1, k):
+    """The scan skips storing blocks below its running bound of the k-th best score
+    (one-block bound up to k=64, two-block bound up to k=128, none above)."""
+    w, h, idx = c1
+    q = W.queries(w, batch=6)
+    try:
+        idx.set_option("scan_prune", 0)
+        say(f"C1 k={k} without store pruning")
+        ref = gpu_search(idx, q, 16, k)
+        idx.set_option("scan_prune", 2)       # forced: C1's plan is below the size where it switches on
+        for rep in range(2):
+            say(f"C1 k={k} with store pruning, run {rep}")
+            got = gpu_search(idx, q, 16, k)
+            assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    finally:
+        idx.set_option("scan_prune", 1)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, 16, k, ref, w.storage)
 
 
 def test_error_paths_on_the_gpu(c1):
