@@ -91,10 +91,19 @@ int ivf_index_upload_end(ivf_index *idx);
  * number of resident database partitions, Section 4.2).  Lists are ranked by
  * (length descending, list number ascending) and stay HBM-resident, in that order,
  * while their padded size still fits in `bytes`; all others are moved to pinned host
- * memory and are streamed to the GPU per search batch.  INT64_MAX (or anything at
- * least the index size) makes everything resident again.  Results of ivf_search do
- * not depend on the budget.  Blocks until the move is done.  On failure the previous
- * placement is kept.
+ * memory and cross PCIe once per search batch that probes them.  Two ways, chosen with
+ * ivf_set_option("host_direct", ...):
+ *   1 (default)  the scan kernel reads them in place from pinned host memory, in the same
+ *                launch as the HBM-resident lists (measured ~56 GB/s, 97 % of the box's
+ *                pinned host-to-device copy rate);
+ *   0            they are copied with hipMemcpyAsync on a side stream into a ring of
+ *                staging buffers ("stage_mb", "nstage"), neighbouring lists merged into
+ *                one copy, and each chunk is scanned on the caller's stream as soon as its
+ *                event fires, while the resident lists are scanned meanwhile (measured
+ *                36-43 GB/s: one copy call per ~2 MB list dominates).
+ * INT64_MAX (or anything at least the index size) makes everything resident again.
+ * Results of ivf_search do not depend on the budget or on the mode.  Blocks until the
+ * move is done.  On failure the previous placement is kept.
  */
 int ivf_set_device_budget(ivf_index *idx, int64_t bytes);
 
@@ -109,11 +118,11 @@ int ivf_set_device_budget(ivf_index *idx, int64_t bytes);
  *               than k candidates exist
  *   out_scores  [nq, k] fp32 DEVICE pointer: inner products; -inf where padded
  *   stream      hipStream_t (NULL = default stream).  Work is enqueued on it; the
- *               outputs are valid once the caller has synchronised it.  When every
- *               list is HBM-resident and the scratch buffers are already large
- *               enough the call does not block; with host-resident lists it blocks
- *               until their copies have been issued (it uses one internal side
- *               stream for them and joins it to `stream` with events).
+ *               outputs are valid once the caller has synchronised it.  The call does
+ *               not block once the scratch buffers are large enough, except in the
+ *               staged host-list mode ("host_direct" = 0), where it blocks until the
+ *               copies of the probed host-resident lists have been issued (one internal
+ *               side stream, joined to `stream` with events).
  * The first call (and any call with a larger nq*nprobe or k than before) allocates
  * scratch memory; later calls reuse it.
  */
@@ -191,8 +200,12 @@ int ivf_debug_copy(void *dst, const void *src, int64_t bytes, void *stream);
    for ordinary data. */
 int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
 
-/* Tuning knobs for experiments (launch shape of the scan kernel etc.); unknown names
-   return IVF_ERR_INVALID.  Defaults are the tuned values. */
+/* Tuning knobs; unknown names or values return IVF_ERR_INVALID.  Defaults are the tuned
+   values.  "host_direct" 0|1 (see ivf_set_device_budget), "stage_mb" 1..4096, "nstage"
+   2..8, "nside" 1..4 (copy streams of the staged mode), "scan_unroll" 8|16 (16-byte
+   loads per lane and register buffer), "scan_waves" 1|2|4|8 (wavefronts per workgroup),
+   "scan_mode" 0|1 (1 = persistent wavefronts on an atomic queue, "scan_wgs_per_cu"
+   1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always). */
 int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
 
 #ifdef __cplusplus

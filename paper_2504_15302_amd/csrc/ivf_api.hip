@@ -97,6 +97,7 @@ struct Scratch {
 };
 
 constexpr int kMaxStage = 8;
+constexpr int kMaxSide = 4;
 constexpr int kTimingSlots = 64;   // searches whose stage events are kept
 constexpr int kEvPerSearch = 7;    // stage boundaries 0..6
 
@@ -131,7 +132,7 @@ struct ivf_index {
     size_t h_arena_bytes = 0;
     int64_t resident_lists = 0;
     // streaming of host-resident lists
-    hipStream_t side = nullptr;
+    hipStream_t side[kMaxSide] = {};   // copy streams for host-resident lists (chunks alternate)
     char* stage[kMaxStage] = {};
     hipEvent_t stage_ready[kMaxStage] = {}, stage_free[kMaxStage] = {};
     bool stage_used[kMaxStage] = {};
@@ -151,7 +152,7 @@ struct ivf_index {
     bool ev_created = false;
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_stage_mb = 64,
+    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_stage_mb = 64,
             opt_nstage = 3;
 };
 
@@ -205,9 +206,14 @@ int dalloc(T*& p, size_t count, size_t& total) {
     return 0;
 }
 
+// Device table of list addresses.  A host-resident list has a null entry, or — when the
+// scan is to read pinned host memory directly — its host address tagged in bit 0.
 int upload_list_ptr_table(ivf_index* x) {
-    HIP_TRY(hipMemcpy(x->d_list_ptr, x->dev_ptr.data(), sizeof(void*) * (size_t)x->nlist,
-                      hipMemcpyHostToDevice));
+    std::vector<const char*> tab(x->dev_ptr);
+    if (x->opt_host_direct)
+        for (int64_t l = 0; l < x->nlist; ++l)
+            if (!tab[l] && x->host_ptr[l]) tab[l] = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(x->host_ptr[l]) | 1u);
+    HIP_TRY(hipMemcpy(x->d_list_ptr, tab.data(), sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice));
     return 0;
 }
 
@@ -349,7 +355,8 @@ int ensure_staging(ivf_index* x) {
 int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipStream_t st) {
     Scratch& s = x->sc;
     HIP_TRY(hipEventSynchronize(x->ev_probes));
-    HIP_TRY(hipStreamSynchronize(x->side));   // pinned item mirror of the previous search is free
+    const int nside = (int)std::min<int64_t>(kMaxSide, std::max<int64_t>(1, x->opt_nside));
+    for (int i = 0; i < kMaxSide; ++i) HIP_TRY(hipStreamSynchronize(x->side[i]));   // pinned item mirror of the previous search is free
     const size_t npairs = (size_t)nq * nprobe;
     std::vector<std::pair<int32_t, uint32_t>> pl(npairs);
     for (size_t f = 0; f < npairs; ++f) pl[f] = {s.h_probes[f], (uint32_t)f};
@@ -381,13 +388,15 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
         sb += cnt * (uint32_t)x->nblk[l];
         i = j;
     }
-    if (x->done_recorded) HIP_TRY(hipStreamWaitEvent(x->side, x->ev_done, 0));
+    if (x->done_recorded)
+        for (int i = 0; i < nside; ++i) HIP_TRY(hipStreamWaitEvent(x->side[i], x->ev_done, 0));
 
     size_t item_off = 0;
     size_t i = 0;
     int chunk = 0;
     while (i < hl.size()) {
         const int slot = chunk % x->nstage;
+        hipStream_t side = x->side[chunk % nside];
         size_t used = 0, j = i;
         while (j < hl.size()) {
             size_t b = (size_t)x->nblk[hl[j].l] * x->block_bytes;
@@ -396,7 +405,7 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
             ++j;
         }
         if (j == i) return fail(IVF_ERR_LIMIT, "staging buffer smaller than a list");
-        if (x->stage_used[slot]) HIP_TRY(hipStreamWaitEvent(x->side, x->stage_free[slot], 0));
+        if (x->stage_used[slot]) HIP_TRY(hipStreamWaitEvent(side, x->stage_free[slot], 0));
         // copies: merge lists that are neighbours in the host arena
         size_t dst_off = 0;
         size_t a = i;
@@ -409,7 +418,7 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
                 bytes += (size_t)x->nblk[hl[e].l] * x->block_bytes;
                 ++e;
             }
-            HIP_TRY(hipMemcpyAsync(x->stage[slot] + dst_off, src, bytes, hipMemcpyHostToDevice, x->side));
+            HIP_TRY(hipMemcpyAsync(x->stage[slot] + dst_off, src, bytes, hipMemcpyHostToDevice, side));
             dst_off += bytes;
             a = e;
         }
@@ -437,8 +446,8 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
         }
         const size_t nitems = item_off - item_begin;
         HIP_TRY(hipMemcpyAsync(s.stream_items + item_begin, s.h_items + item_begin,
-                               nitems * sizeof(ScanItem), hipMemcpyHostToDevice, x->side));
-        HIP_TRY(hipEventRecord(x->stage_ready[slot], x->side));
+                               nitems * sizeof(ScanItem), hipMemcpyHostToDevice, side));
+        HIP_TRY(hipEventRecord(x->stage_ready[slot], side));
         HIP_TRY(hipStreamWaitEvent(st, x->stage_ready[slot], 0));
         launch_scan(x, nitems, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q, 0);
         HIP_TRY(hipGetLastError());
@@ -471,7 +480,7 @@ int ivf_index_create(ivf_index** out) {
     hipError_t e = hipGetDevice(&x->device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, x->device);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->side, hipStreamNonBlocking);
+    for (int i = 0; e == hipSuccess && i < kMaxSide; ++i) e = hipStreamCreateWithFlags(&x->side[i], hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_probes, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_done, hipEventDisableTiming);
     for (int i = 0; e == hipSuccess && i < kMaxStage; ++i) {
@@ -493,7 +502,8 @@ void ivf_index_destroy(ivf_index* x) {
     if (!x) return;
     (void)hipDeviceSynchronize();
     free_index_data(x);
-    if (x->side) (void)hipStreamDestroy(x->side);
+    for (int i = 0; i < kMaxSide; ++i)
+        if (x->side[i]) (void)hipStreamDestroy(x->side[i]);
     if (x->ev_probes) (void)hipEventDestroy(x->ev_probes);
     if (x->ev_done) (void)hipEventDestroy(x->ev_done);
     for (int i = 0; i < kMaxStage; ++i) {
@@ -802,7 +812,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     if ((uint64_t)nq * (uint64_t)nprobe >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "nq*nprobe above 2^31");
     if ((uint64_t)block_bound(x, nq, nprobe) >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "batch too large for one call");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool offload = x->resident_lists < x->nlist;
+    const bool offload = x->resident_lists < x->nlist && !x->opt_host_direct;
     if (offload && (rc = ensure_staging(x))) return rc;
     if ((rc = ensure_scratch(x, nq, nprobe, offload))) return rc;
     Scratch& s = x->sc;
@@ -863,7 +873,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
                        x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
                        s.pair_flat, s.pair_of_probe, s.items);
     mark();   // 3
-    if (x->resident_lists > 0) {
+    if (x->resident_lists > 0 || x->opt_host_direct) {
         const int mode = (int)x->opt_scan_mode;
         const int64_t bound = std::max<int64_t>(1, block_bound(x, nq, nprobe));
         launch_scan(x, (size_t)bound, st, s.items, s.counters + kCntItems, 0, queries, mode);
@@ -1052,6 +1062,19 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     else if (n == "scan_waves" && (value == 1 || value == 2 || value == 4 || value == 8)) x->opt_scan_waves = value;
     else if (n == "scan_wgs_per_cu" && value >= 1 && value <= 16) x->opt_scan_wgs_per_cu = value;
     else if (n == "scan_prune" && value >= 0 && value <= 2) x->opt_scan_prune = value;   // 2 = also on small plans
+    else if (n == "host_direct" && (value == 0 || value == 1)) {
+        // 1: the scan kernel reads host-resident lists straight from pinned host memory
+        // (no staging copies); 0: they are copied with hipMemcpyAsync on the side stream
+        if (x->opt_host_direct != value) {
+            x->opt_host_direct = value;
+            if (x->ready) {
+                HIP_TRY(hipDeviceSynchronize());
+                int rc = upload_list_ptr_table(x);
+                if (rc) return rc;
+            }
+        }
+    }
+    else if (n == "nside" && value >= 1 && value <= kMaxSide) x->opt_nside = value;
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
     else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);

@@ -54,7 +54,9 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
         const unsigned cnt = h & kHistCountMask;
         if (cnt) {
             unsigned nb = (unsigned)nblk[l];
-            bool res = list_ptr[l] != nullptr;
+            const uintptr_t lp = reinterpret_cast<uintptr_t>(list_ptr[l]);
+            bool res = lp != 0;                      // readable by the scan kernel
+            const bool in_hbm = res && !(lp & 1u);   // bit 0 tags a pinned-host address
             first = (h >> kHistTopShift) != 0;
             v[0] = cnt;
             v[1] = cnt * nb;
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
             v[first ? 2 : 3] = items;
             uniq = 1;
             vec = (unsigned)len[l];
-            vres = res ? vec : 0;
+            vres = in_hbm ? vec : 0;
         }
     }
     if (t == 0) extra[0] = extra[1] = extra[2] = 0;
@@ -181,7 +183,7 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
     for (unsigned i = 0; i < cnt; ++i) {
         pair_of_probe[seg[i]] = ps + i;
     }
-    const char* base = static_cast<const char*>(list_ptr[l]);
+    const char* base = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(list_ptr[l]) & ~(uintptr_t)1);
     if (!base) return;
     const unsigned nb = (unsigned)nblk[l];
     const unsigned ln = (unsigned)len[l];

@@ -207,6 +207,25 @@ def test_results_do_not_depend_on_placement(c1):
             vec, ids = idx.read_list(l, w.d, ivf.IVF_FP32)
             assert np.array_equal(vec, h.vectors[h.offsets[l]:h.offsets[l + 1]])
     check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, w.k, ref, w.storage)
+    # the same with host-resident lists copied to staging buffers with hipMemcpyAsync on
+    # the side stream (default: the scan reads them in place from pinned host memory)
+    try:
+        idx.set_option("host_direct", 0)
+        for frac, stage_mb, nstage in ((0.3, 64, 3), (0.0, 1, 2), (0.5, 2, 4)):
+            idx.set_option("stage_mb", stage_mb)
+            idx.set_option("nstage", nstage)
+            idx.set_device_budget(int(total * frac))
+            for rep in range(2):
+                say(f"C1 device budget {frac:.2f}, staged copies ({nstage} x {stage_mb} MiB), run {rep}")
+                got = gpu_search(idx, q, w.nprobe, w.k)
+                assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+            st = idx.last_search_stats()
+            assert st.scan_bytes_streamed > 0 and st.scan_bytes_resident + st.scan_bytes_streamed == st.scan_bytes
+    finally:
+        idx.set_option("host_direct", 1)
+        idx.set_option("stage_mb", 64)
+        idx.set_option("nstage", 3)
+        idx.set_device_budget(2**62)
 
 
 def test_scan_launch_options_agree(c1):
