@@ -21,6 +21,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per k_scan launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE, both
+# scaled against the library's plain copy kernel): profiles/k_scan_C5_pmc_traffic.md.
+# Only the default workload has been counted; the others report null.
+TRAFFIC_BYTES = {"C5": 1.66726e7 * 2.000 * 1024 + 5510.66 * 1024}
 
 
 def log(msg):
@@ -180,6 +184,7 @@ def main():
     qps = w.nq / (ms_per_step / 1e3)
 
     # per-kernel view of the same timed steps (HIP events on the search's stream)
+    direct = not any(o.replace(" ", "") == "host_direct=0" for o in args.option)   # library default: direct
     kept = min(args.steps, 64)
     stage_sum = {}
     scan_ms, scan_bytes = [], []
@@ -190,7 +195,8 @@ def main():
             stage_sum[name] = stage_sum.get(name, 0.0) + v
         st = stats[step % nb]
         scan_ms.append(ms["scan"])
-        scan_bytes.append(st.scan_bytes_resident)
+        # with host lists read in place, the one scan launch covers both HBM and PCIe bytes
+        scan_bytes.append(st.scan_bytes if direct else st.scan_bytes_resident)
     stage_avg = {name: v / kept for name, v in stage_sum.items()}
     avg_scan_ms = float(np.mean(scan_ms))
     avg_scan_bytes = float(np.mean(scan_bytes))
@@ -213,7 +219,10 @@ def main():
                    "scan_bytes_streamed_per_batch": int(st0.scan_bytes_streamed)},
         "roofline": {"bound": "hbm", "kernel": "k_scan (scan of HBM-resident probed lists)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES.get(w.name) if not args.option else None,
+                     "traffic_source": "profiles/k_scan_C5_pmc_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                                       "bytes per launch)" if (w.name in TRAFFIC_BYTES and not args.option) else None,
                      "bytes_per_launch": avg_scan_bytes, "ms_per_launch": avg_scan_ms,
                      "launches_timed": kept,
                      "plain_read_same_pattern_GBps": read_ceiling},
@@ -236,9 +245,10 @@ def main():
         h2d = 4 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del hsrc, ddst
         streamed = float(np.mean([stats[(args.steps - 1 - b) % nb].scan_bytes_streamed for b in range(kept)]))
-        direct = not any(o.replace(" ", "") == "host_direct=0" for o in args.option)   # library default: direct
         t_stream = stage_avg["scan"] if direct else stage_avg["stream"]   # direct reads happen inside the scan
         rate = streamed / 1e9 / (t_stream * 1e-3) if t_stream > 0 else None
+        result["roofline"]["note"] = ("this workload is PCIe-bound: most probed bytes come from pinned host memory; "
+                                      "see the pcie object, the HBM figure is not meaningful here")
         result["pcie"] = {"streamed_GB_per_batch": streamed / 1e9, "GBps_over_stream_stage": rate,
                           "mode": "scan reads pinned host memory directly" if direct else "hipMemcpyAsync to staging on a side stream",
                           "pinned_h2d_copy_GBps_1GiB": h2d, "frac_of_h2d_copy": rate / h2d if rate else None}
