@@ -143,6 +143,39 @@ def test_many_queries_share_one_list():
     idx.close()
 
 
+@pytest.mark.parametrize("nq", [33, 64, 65, 129, 300])
+def test_batch_sizes_across_the_coarse_kernel_tilings(c1, nq):
+    """nq <= 32, <= 64 and above take different query-tile shapes in the coarse kernel;
+    above 128 the grid gets a second row of workgroups."""
+    w, h, idx = c1
+    q = W.queries(w, batch=7, nq=nq)
+    say(f"C1 nq={nq} nprobe=4 k=7")
+    got = gpu_search(idx, q, 4, 7)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, 4, 7, got, w.storage)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_shapes_match_oracle(seed):
+    """Seeded random shapes: list count, dimension, storage type, batch, nprobe and k."""
+    rng = np.random.default_rng(1000 + seed)
+    nlist = int(rng.integers(1, 90))
+    d = 8 * int(rng.integers(1, 40))
+    n = int(rng.integers(1, 20000))
+    storage = "fp16" if rng.integers(2) else "fp32"
+    nq = int(rng.integers(1, 70))
+    nprobe = int(rng.integers(1, nlist + 3))
+    k = int(rng.integers(1, 300))
+    cen, vec, ids, off = _random_index(seed, n, d, nlist, storage)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    idx = ivf.Index()
+    idx.upload(cen, vec, ids, off)
+    idx.set_option("scan_prune", 2)
+    say(f"random case {seed}: n={n} d={d} nlist={nlist} {storage} nq={nq} nprobe={nprobe} k={k}")
+    got = gpu_search(idx, q, nprobe, k)
+    check_against_oracle(cen, vec, ids, off, q, nprobe, k, got, storage, abs_floor=_floor(q, vec))
+    idx.close()
+
+
 def test_exact_ties_go_to_the_smaller_id():
     d = 16
     rng = np.random.default_rng(8)
