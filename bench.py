@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel over this many MiB (reference "
                          "point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time ivf_search at batch sizes 8..nq, fit T(B) = a*B^c and report the "
+                         "backlog-aware batch-size choice (ivf_sched_*)")
     ap.add_argument("--read-ceiling-gib", type=int, default=24,
                     help="size of the plain streaming-read measurement (0 skips it)")
     args = ap.parse_args()
@@ -252,6 +255,27 @@ def main():
         result["pcie"] = {"streamed_GB_per_batch": streamed / 1e9, "GBps_over_stream_stage": rate,
                           "mode": "scan reads pinned host memory directly" if direct else "hipMemcpyAsync to staging on a side stream",
                           "pinned_h2d_copy_GBps_1GiB": h2d, "frac_of_h2d_copy": rate / h2d if rate else None}
+    if args.batch_sweep:
+        from paper_2504_15302_amd import ivf as ivf_mod
+        sizes = [b for b in (8, 16, 32, 64, 128, 256) if b <= w.nq]
+        times = []
+        for b in sizes:
+            qs = [q[:b].contiguous() for q in q_dev]
+            oi, os_ = out_ids[:b].contiguous(), out_scores[:b].contiguous()
+            for i in range(2):
+                idx.search(qs[i % nb], w.nprobe, w.k, oi, os_)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(8):
+                idx.search(qs[i % nb], w.nprobe, w.k, oi, os_)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) / 8 * 1e3)
+        a, c = ivf_mod.sched_fit(sizes, times)
+        best, lat = ivf_mod.sched_choose(a, c, w.nq, sizes)
+        result["batch_scheduling"] = {
+            "batch_sizes": sizes, "ms_per_search": times, "fit_a_ms": a, "fit_c": c,
+            "queue": w.nq, "chosen_batch": best, "avg_latency_ms_from_queue_start": lat,
+            "single_batch_beats_two": ivf_mod.sched_single_batch_is_best(c, 2)}
     if args.cpu_seconds > 0:
         log("timing the CPU oracle on a sample of batch 0")
         result["cpu_baseline"] = cpu_baseline(lw, idx, q_host[0], first[0], first[1], w.nprobe, w.k, args.cpu_seconds)

@@ -208,6 +208,36 @@ int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
    1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always). */
 int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
 
+/* ---- batch-size choice for the retrieval worker (host arithmetic, no GPU) ----
+ *
+ * Backlog-aware batch scheduling (paper Section 4.4, Eq. 4-8).  T(B) = a * B^c models
+ * the time of one ivf_search over a batch of B queries; with n requests queued, k equal
+ * batches served in turn give an average latency of (k+1)/2 * T(n/k) - mean arrival time
+ * (Eq. 5 for k = 1, Eq. 6); one batch is at least as good as k batches iff
+ * 2 k^c <= k+1 (Eq. 7; c <= log2(3/2) for k = 2, Eq. 8).
+ */
+
+/* Least-squares fit of log T = log a + c log B to m >= 1 measured samples (all > 0);
+   m = 1 or equal batch sizes give c = 0. */
+int ivf_sched_fit(const double *batch_sizes, const double *times, int m, double *a, double *c);
+
+/* T(B) = a * B^c. */
+double ivf_sched_batch_time(double a, double c, double batch_size);
+
+/* Average latency of n queued requests served as k equal batches (Eq. 5, 6);
+   mean_arrival = (1/n) sum t_i, in the unit of a. */
+int ivf_sched_avg_latency(double a, double c, int64_t n, int64_t k, double mean_arrival, double *latency);
+
+/* 1 if one batch is at least as good as k equal batches (Eq. 7), 0 if not, < 0 on error. */
+int ivf_sched_single_batch_is_best(double c, int64_t k);
+
+/* Scores every candidate batch size for a queue of n requests and returns the best
+   (ties to the larger batch).  A candidate B < n is served as ceil(n/B) batches of B, the
+   last one partly empty: (k+1)/2 * T(B) - mean_arrival; a candidate >= n as one batch of
+   n.  best_latency may be NULL. */
+int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, int m, double mean_arrival,
+                     int64_t *best_batch, double *best_latency);
+
 #ifdef __cplusplus
 }
 #endif

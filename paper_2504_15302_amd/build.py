@@ -46,6 +46,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
                 print(" ".join(cmd), flush=True)
             subprocess.check_call(cmd)
         objs.append(obj)
+    sched_src = os.path.join(CSRC, "ivf_sched.cpp")          # host-only arithmetic
+    sched_obj = os.path.join(OBJ_DIR, "ivf_sched.o")
+    cmd = ["hipcc", "-O2", "-fPIC", "-std=c++17", "-c", sched_src, "-o", sched_obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    objs.append(sched_obj)
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -26,6 +26,8 @@ EXPORTS = (
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
     "ivf_set_option", "ivf_debug_copy", "ivf_debug_read",
+    "ivf_sched_fit", "ivf_sched_batch_time", "ivf_sched_avg_latency", "ivf_sched_single_batch_is_best",
+    "ivf_sched_choose",
 )
 
 
@@ -87,9 +89,16 @@ def load_library() -> C.CDLL:
     lib.ivf_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.ivf_debug_copy.argtypes = [vp, vp, i64, vp]
     lib.ivf_debug_read.argtypes = [vp, i64, vp, vp]
+    dbl, pd, pi64 = C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_int64)
+    lib.ivf_sched_fit.argtypes = [pd, pd, i32, pd, pd]
+    lib.ivf_sched_batch_time.argtypes = [dbl, dbl, dbl]
+    lib.ivf_sched_avg_latency.argtypes = [dbl, dbl, i64, i64, dbl, pd]
+    lib.ivf_sched_single_batch_is_best.argtypes = [dbl, i64]
+    lib.ivf_sched_choose.argtypes = [dbl, dbl, i64, pi64, i32, dbl, pi64, pd]
     for name in EXPORTS:
-        if name not in ("ivf_index_destroy", "ivf_last_error"):
+        if name not in ("ivf_index_destroy", "ivf_last_error", "ivf_sched_batch_time"):
             getattr(lib, name).restype = C.c_int
+    lib.ivf_sched_batch_time.restype = dbl
     _lib = lib
     return lib
 
@@ -242,3 +251,44 @@ class Index:
 
     def set_option(self, name: str, value: int):
         _check(self._lib.ivf_set_option(self._h, name.encode(), int(value)))
+
+
+# ---- batch-size choice for the retrieval worker (ivf_sched_*: host arithmetic, no GPU)
+
+def sched_fit(batch_sizes, times):
+    """(a, c) of T(B) = a * B**c fitted to measured samples."""
+    m = len(batch_sizes)
+    bs = (C.c_double * m)(*[float(b) for b in batch_sizes])
+    ts = (C.c_double * m)(*[float(t) for t in times])
+    a, c = C.c_double(), C.c_double()
+    _check_plain(load_library().ivf_sched_fit(bs, ts, m, C.byref(a), C.byref(c)))
+    return a.value, c.value
+
+
+def sched_batch_time(a: float, c: float, batch_size: float) -> float:
+    return float(load_library().ivf_sched_batch_time(a, c, batch_size))
+
+
+def sched_avg_latency(a: float, c: float, n: int, k: int, mean_arrival: float = 0.0) -> float:
+    out = C.c_double()
+    _check_plain(load_library().ivf_sched_avg_latency(a, c, n, k, mean_arrival, C.byref(out)))
+    return out.value
+
+
+def sched_single_batch_is_best(c: float, k: int) -> bool:
+    rc = load_library().ivf_sched_single_batch_is_best(c, k)
+    _check_plain(rc if rc < 0 else 0)
+    return rc == 1
+
+
+def sched_choose(a: float, c: float, n: int, candidates, mean_arrival: float = 0.0):
+    m = len(candidates)
+    cs = (C.c_int64 * m)(*[int(x) for x in candidates])
+    best, lat = C.c_int64(), C.c_double()
+    _check_plain(load_library().ivf_sched_choose(a, c, n, cs, m, mean_arrival, C.byref(best), C.byref(lat)))
+    return best.value, lat.value
+
+
+def _check_plain(rc: int):
+    if rc != 0:
+        raise IvfError(rc, "invalid argument to an ivf_sched_* function")
