@@ -102,8 +102,19 @@ int ivf_index_upload_end(ivf_index *idx);
  *                event fires, while the resident lists are scanned meanwhile (measured
  *                36-43 GB/s: one copy call per ~2 MB list dominates).
  * INT64_MAX (or anything at least the index size) makes everything resident again.
- * Results of ivf_search do not depend on the budget or on the mode.  Blocks until the
- * move is done.  On failure the previous placement is kept.
+ * Results of ivf_search do not depend on the budget or on the mode.
+ *
+ * The call may be repeated at any time between searches (the paper changes the number of
+ * resident partitions between retrieval batches, Sections 4.2 and 5): only the lists that
+ * change tier are copied across PCIe.  List data lives in pools of segments (a sixteenth
+ * of the index each, between 64 MiB and "segment_mb", default 2048); after evictions the
+ * least-filled HBM segments are emptied into the holes of the others with device-to-device
+ * copies and freed, so the HBM actually held (ivf_info.device_pool_bytes) follows the
+ * budget to within about one segment and no second copy of a tier ever exists.
+ * ivf_set_option("residency_policy", 1) ranks lists by how often they have been probed so
+ * far (then length, then number) instead of by length.  Blocks until the move is done.
+ * If memory runs out half-way the lists moved so far stay where they are (every list
+ * always has exactly one valid place) and the error is returned.
  */
 int ivf_set_device_budget(ivf_index *idx, int64_t bytes);
 
@@ -143,6 +154,11 @@ typedef struct {
     int64_t host_list_bytes;    /* padded list data in pinned host memory */
     int64_t resident_lists;
     int64_t scratch_bytes;      /* search scratch currently allocated */
+    int64_t device_pool_bytes;  /* HBM held by the list pool (whole segments, >= device_list_bytes) */
+    int64_t host_pool_bytes;    /* pinned host memory held by the list pool */
+    int64_t moved_h2d_bytes;    /* last ivf_set_device_budget: bytes copied host -> HBM, */
+    int64_t moved_d2h_bytes;    /*   HBM -> host, */
+    int64_t moved_d2d_bytes;    /*   and inside HBM while compacting the pool */
 } ivf_info;
 int ivf_get_info(ivf_index *idx, ivf_info *out);
 

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <limits>
+#include <map>
 #include <new>
 #include <numeric>
 #include <string>
@@ -101,6 +102,31 @@ constexpr int kMaxSide = 4;
 constexpr int kTimingSlots = 64;   // searches whose stage events are kept
 constexpr int kEvPerSearch = 7;    // stage boundaries 0..6
 
+// List data lives in pools of fixed-size segments (one hipMalloc / hipHostMalloc each),
+// carved in units of one 64-vector block.  A list is contiguous inside one segment.
+// Segments let a change of the device budget move only the lists that change tier and
+// hand memory back segment by segment, without ever holding a second copy of a tier.
+struct Seg {
+    char* base = nullptr;
+    size_t blocks = 0, used = 0;
+    std::map<size_t, size_t> free;   // offset -> length, in blocks, coalesced
+};
+struct Pool {
+    bool device = true;
+    size_t block_bytes = 0, seg_blocks = 0;
+    std::vector<Seg> segs;           // a dropped segment keeps its slot (base == nullptr)
+    size_t allocated_blocks() const {
+        size_t n = 0;
+        for (const Seg& g : segs) n += g.blocks;
+        return n;
+    }
+};
+struct Loc {
+    int8_t tier = 0;                 // 0 = HBM, 1 = pinned host
+    int32_t seg = -1;                // -1: the list is empty
+    size_t off = 0;                  // in blocks
+};
+
 }  // namespace
 
 struct ivf_index {
@@ -114,23 +140,21 @@ struct ivf_index {
     std::vector<int64_t> offsets, blk_off;
     std::vector<int32_t> len, nblk;
     std::vector<int64_t> top_nblk_prefix;       // prefix sums of nblk sorted descending
-    std::vector<const char*> dev_ptr, host_ptr; // per list: where its blocks live
+    std::vector<const char*> dev_ptr, host_ptr; // per list: where its blocks live (derived from loc)
+    std::vector<Loc> loc;
+    Pool dpool, hpool;
     // device tables
     float* d_centroids = nullptr;
     int64_t* d_offsets = nullptr;
-    int64_t* d_blk_off = nullptr;
     int32_t* d_len = nullptr;
     int32_t* d_nblk = nullptr;
     const void** d_list_ptr = nullptr;
     int64_t* d_ids_pos = nullptr;      // only while uploading
     int64_t* d_id_sorted = nullptr;
     uint32_t* d_rank_of_pos = nullptr;
-    // list data
-    char* d_arena = nullptr;
-    size_t d_arena_bytes = 0;
-    char* h_arena = nullptr;
-    size_t h_arena_bytes = 0;
+    uint32_t* d_hits = nullptr;        // per list: how often it has been probed (residency policy)
     int64_t resident_lists = 0;
+    int64_t moved_h2d = 0, moved_d2h = 0, moved_d2d = 0;   // bytes moved by the last budget change
     // streaming of host-resident lists
     hipStream_t side[kMaxSide] = {};   // copy streams for host-resident lists (chunks alternate)
     char* stage[kMaxStage] = {};
@@ -152,11 +176,105 @@ struct ivf_index {
     bool ev_created = false;
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_stage_mb = 64,
+    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
             opt_nstage = 3;
 };
 
 namespace {
+
+void pool_free_all(Pool& p) {
+    for (Seg& g : p.segs)
+        if (g.base) { if (p.device) (void)hipFree(g.base); else (void)hipHostFree(g.base); }
+    p.segs.clear();
+}
+
+// New segment of `blocks` blocks; returns its index or -1 when the allocation fails.
+int pool_new_seg(Pool& p, size_t blocks) {
+    char* base = nullptr;
+    const size_t bytes = blocks * p.block_bytes;
+    hipError_t e = p.device ? hipMalloc(reinterpret_cast<void**>(&base), bytes)
+                            : hipHostMalloc(reinterpret_cast<void**>(&base), bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    int idx = -1;
+    for (size_t i = 0; i < p.segs.size(); ++i)
+        if (!p.segs[i].base) { idx = (int)i; break; }
+    if (idx < 0) { p.segs.emplace_back(); idx = (int)p.segs.size() - 1; }
+    Seg& g = p.segs[idx];
+    g.base = base; g.blocks = blocks; g.used = 0;
+    g.free.clear();
+    g.free[0] = blocks;
+    return idx;
+}
+
+// First fit over the existing segments (skipping `exclude`), then a new segment if allowed.
+bool pool_alloc(Pool& p, size_t n, int& seg, size_t& off, bool may_grow, int exclude = -1) {
+    for (size_t i = 0; i < p.segs.size(); ++i) {
+        Seg& g = p.segs[i];
+        if (!g.base || (int)i == exclude || g.blocks - g.used < n) continue;
+        for (auto it = g.free.begin(); it != g.free.end(); ++it) {
+            if (it->second < n) continue;
+            const size_t o = it->first, len = it->second;
+            g.free.erase(it);
+            if (len > n) g.free[o + n] = len - n;
+            g.used += n;
+            seg = (int)i; off = o;
+            return true;
+        }
+    }
+    if (!may_grow) return false;
+    int idx = pool_new_seg(p, std::max(p.seg_blocks, n));
+    if (idx < 0 && p.seg_blocks > n) idx = pool_new_seg(p, n);
+    if (idx < 0) return false;
+    Seg& g = p.segs[idx];
+    g.free.clear();
+    if (g.blocks > n) g.free[n] = g.blocks - n;
+    g.used = n;
+    seg = idx; off = 0;
+    return true;
+}
+
+void pool_release(Pool& p, int seg, size_t off, size_t n) {
+    Seg& g = p.segs[seg];
+    auto it = g.free.emplace(off, n).first;
+    auto nx = std::next(it);
+    if (nx != g.free.end() && it->first + it->second == nx->first) {
+        it->second += nx->second;
+        g.free.erase(nx);
+    }
+    if (it != g.free.begin()) {
+        auto pv = std::prev(it);
+        if (pv->first + pv->second == it->first) {
+            pv->second += it->second;
+            g.free.erase(it);
+        }
+    }
+    g.used -= n;
+}
+
+void pool_drop_empty(Pool& p) {
+    for (Seg& g : p.segs)
+        if (g.base && g.used == 0) {
+            if (p.device) (void)hipFree(g.base); else (void)hipHostFree(g.base);
+            g = Seg();
+        }
+}
+
+void refresh_list_ptrs(ivf_index* x) {
+    for (int64_t l = 0; l < x->nlist; ++l) {
+        const Loc& c = x->loc[l];
+        x->dev_ptr[l] = x->host_ptr[l] = nullptr;
+        if (c.seg < 0) {     // empty list: a non-null device address marks it resident
+            if (c.tier == 0) x->dev_ptr[l] = reinterpret_cast<const char*>(x->d_centroids);
+            continue;
+        }
+        const Pool& p = c.tier == 0 ? x->dpool : x->hpool;
+        const char* a = p.segs[c.seg].base + c.off * p.block_bytes;
+        (c.tier == 0 ? x->dev_ptr : x->host_ptr)[l] = a;
+    }
+}
 
 void free_scratch(Scratch& s) {
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
@@ -180,12 +298,11 @@ void free_staging(ivf_index* x) {
 }
 
 void free_index_data(ivf_index* x) {
-    dfree(x->d_centroids); dfree(x->d_offsets); dfree(x->d_blk_off); dfree(x->d_len);
+    dfree(x->d_centroids); dfree(x->d_offsets); dfree(x->d_len);
     dfree(x->d_nblk); dfree(x->d_list_ptr); dfree(x->d_ids_pos); dfree(x->d_id_sorted);
-    dfree(x->d_rank_of_pos); dfree(x->d_arena);
-    if (x->h_arena) (void)hipHostFree(x->h_arena);
-    x->h_arena = nullptr;
-    x->d_arena_bytes = x->h_arena_bytes = 0;
+    dfree(x->d_rank_of_pos); dfree(x->d_hits);
+    pool_free_all(x->dpool);
+    pool_free_all(x->hpool);
     free_staging(x);
     free_scratch(x->sc);
     x->ready = x->uploading = false;
@@ -538,6 +655,7 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
         x->nblk.assign((size_t)nlist, 0);
         x->dev_ptr.assign((size_t)nlist, nullptr);
         x->host_ptr.assign((size_t)nlist, nullptr);
+        x->loc.assign((size_t)nlist, Loc());
     } catch (const std::bad_alloc&) {
         return fail(IVF_ERR_OOM_HOST, "out of host memory for the list tables");
     }
@@ -566,26 +684,44 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
     int rc;
     if ((rc = dalloc(x->d_centroids, (size_t)nlist * d, tot))) return rc;
     if ((rc = dalloc(x->d_offsets, (size_t)nlist + 1, tot))) return rc;
-    if ((rc = dalloc(x->d_blk_off, (size_t)nlist + 1, tot))) return rc;
     if ((rc = dalloc(x->d_len, (size_t)nlist, tot))) return rc;
     if ((rc = dalloc(x->d_nblk, (size_t)nlist, tot))) return rc;
     if ((rc = dalloc(x->d_list_ptr, (size_t)nlist, tot))) return rc;
     if ((rc = dalloc(x->d_ids_pos, (size_t)n, tot))) return rc;
-    x->d_arena_bytes = std::max<size_t>((size_t)x->total_blocks * x->block_bytes, 256);
+    if ((rc = dalloc(x->d_hits, (size_t)nlist, tot))) return rc;
+    HIP_TRY(hipMemset(x->d_hits, 0, sizeof(uint32_t) * (size_t)nlist));
     {
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&x->d_arena), x->d_arena_bytes);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            x->d_arena = nullptr;
-            return fail(IVF_ERR_OOM_DEVICE, "list arena of %zu bytes: %s", x->d_arena_bytes, hipGetErrorString(e));
+        // segment size: a sixteenth of the index, between 64 MiB and the "segment_mb" option
+        size_t total_bytes = (size_t)x->total_blocks * x->block_bytes;
+        size_t seg_bytes = std::min<size_t>((size_t)x->opt_segment_mb << 20, std::max<size_t>((size_t)64 << 20, total_bytes / 16));
+        size_t max_nb = 1;
+        for (int64_t l = 0; l < nlist; ++l) max_nb = std::max<size_t>(max_nb, (size_t)x->nblk[l]);
+        x->dpool = Pool(); x->hpool = Pool();
+        x->dpool.device = true; x->hpool.device = false;
+        x->dpool.block_bytes = x->hpool.block_bytes = x->block_bytes;
+        x->dpool.seg_blocks = x->hpool.seg_blocks = std::max<size_t>(max_nb, seg_bytes / x->block_bytes);
+        size_t left = (size_t)x->total_blocks;
+        for (int64_t l = 0; l < nlist; ++l) {
+            const size_t nb = (size_t)x->nblk[l];
+            Loc& c = x->loc[l];
+            c.tier = 0;
+            if (!nb) continue;
+            // the last segment is no larger than what is still to be placed
+            x->dpool.seg_blocks = std::max<size_t>(max_nb, std::min(x->dpool.seg_blocks, left));
+            if (!pool_alloc(x->dpool, nb, c.seg, c.off, true)) {
+                pool_free_all(x->dpool);
+                return fail(IVF_ERR_OOM_DEVICE, "out of device memory for the list data (%zu bytes in all)", total_bytes);
+            }
+            left -= nb;
         }
+        x->dpool.seg_blocks = x->hpool.seg_blocks;
     }
     HIP_TRY(hipMemcpy(x->d_centroids, centroids, sizeof(float) * (size_t)nlist * d, hipMemcpyDefault));
     HIP_TRY(hipMemcpy(x->d_offsets, x->offsets.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(x->d_blk_off, x->blk_off.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_len, x->len.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_nblk, x->nblk.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
-    for (int64_t l = 0; l < nlist; ++l) x->dev_ptr[l] = x->d_arena + (size_t)x->blk_off[l] * x->block_bytes;
+    refresh_list_ptrs(x);
+    if ((rc = upload_list_ptr_table(x))) return rc;
     x->resident_lists = nlist;
     x->next_list = 0;
     x->uploading = true;
@@ -636,8 +772,8 @@ int ivf_index_upload_lists(ivf_index* x, int64_t list_begin, int64_t list_end, c
                 }
                 if (e == hipSuccess) {
                     dim3 grid((unsigned)(le - lb), (unsigned)maxnb);
-                    hipLaunchKernelGGL(k_relayout, grid, dim3(256), 0, 0, src, x->d_offsets, x->d_blk_off, lb,
-                                       (int)x->row_bytes, x->d_arena);
+                    hipLaunchKernelGGL(k_relayout, grid, dim3(256), 0, 0, src, x->d_offsets, x->d_list_ptr, lb,
+                                       (int)x->row_bytes);
                     e = hipGetLastError();
                     if (e == hipSuccess) e = hipDeviceSynchronize();
                 }
@@ -707,9 +843,18 @@ int ivf_set_device_budget(ivf_index* x, int64_t bytes) {
     if (bytes < 0) return fail(IVF_ERR_INVALID, "budget must be non-negative");
     HIP_TRY(hipDeviceSynchronize());
     const int64_t nlist = x->nlist;
+    x->moved_h2d = x->moved_d2h = x->moved_d2d = 0;
+
+    // 1. which lists are to be resident: ranked by the policy, while they fit
+    std::vector<uint32_t> hits;
+    if (x->opt_policy == 1) {
+        hits.resize((size_t)nlist);
+        HIP_TRY(hipMemcpy(hits.data(), x->d_hits, sizeof(uint32_t) * (size_t)nlist, hipMemcpyDeviceToHost));
+    }
     std::vector<int32_t> order((size_t)nlist);
     std::iota(order.begin(), order.end(), 0);
     std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (!hits.empty() && hits[a] != hits[b]) return hits[a] > hits[b];
         if (x->len[a] != x->len[b]) return x->len[a] > x->len[b];
         return a < b;
     });
@@ -723,74 +868,115 @@ int ivf_set_device_budget(ivf_index* x, int64_t bytes) {
         res[l] = 1;
         ++nres;
     }
-    bool same = true;
-    for (int64_t l = 0; l < nlist && same; ++l) same = (res[l] != 0) == (x->dev_ptr[l] != nullptr);
-    if (same) return 0;
-    const size_t total = (size_t)x->total_blocks * x->block_bytes;
-    const size_t new_dev = (size_t)used, new_host = total - new_dev;
-    char* nd = nullptr;
-    char* nh = nullptr;
-    if (new_dev) {
-        hipError_t e = hipMalloc(reinterpret_cast<void**>(&nd), new_dev);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            return fail(IVF_ERR_OOM_DEVICE, "new device arena of %zu bytes: %s", new_dev, hipGetErrorString(e));
-        }
-    }
-    if (new_host) {
-        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&nh), new_host);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            if (nd) (void)hipFree(nd);
-            return fail(IVF_ERR_OOM_HOST, "pinned host arena of %zu bytes: %s", new_host, hipGetErrorString(e));
-        }
-    }
-    std::vector<const char*> ndp((size_t)nlist, nullptr), nhp((size_t)nlist, nullptr);
-    size_t doff = 0, hoff = 0;
-    hipError_t e = hipSuccess;
-    // copy runs of lists whose source and destination are both contiguous
-    const char* run_src = nullptr;
-    char* run_dst = nullptr;
-    size_t run_bytes = 0;
-    auto flush = [&]() {
-        if (run_bytes && e == hipSuccess) e = hipMemcpyAsync(run_dst, run_src, run_bytes, hipMemcpyDefault, 0);
-        run_bytes = 0;
-    };
+    std::vector<int32_t> evict, load;
     for (int64_t l = 0; l < nlist; ++l) {
-        size_t b = (size_t)x->nblk[l] * x->block_bytes;
-        const char* src = x->dev_ptr[l] ? x->dev_ptr[l] : x->host_ptr[l];
-        char* dst;
-        if (res[l]) { dst = nd + doff; ndp[l] = dst; doff += b; }
-        else { dst = nh + hoff; nhp[l] = dst; hoff += b; }
-        if (!b) continue;
-        if (run_bytes && src == run_src + run_bytes && dst == run_dst + run_bytes) {
-            run_bytes += b;
-        } else {
-            flush();
-            run_src = src; run_dst = dst; run_bytes = b;
-        }
+        const bool is_res = x->loc[l].tier == 0;
+        if (is_res && !res[l]) evict.push_back((int32_t)l);
+        if (!is_res && res[l]) load.push_back((int32_t)l);
     }
-    flush();
-    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (evict.empty() && load.empty()) return 0;
+
+    // Lists move with asynchronous copies on the default stream; a phase's sources are
+    // released only after the phase has been synchronised.  Only lists that change tier
+    // cross PCIe.  On an allocation failure the lists moved so far keep their new place
+    // (every list is always in exactly one valid place) and the error is returned.
+    struct Move { int32_t l; Loc from, to; };
+    std::vector<Move> moves;
+    hipError_t e = hipSuccess;
+    int err = 0;
+    auto addr = [&](const Loc& c) -> char* {
+        Pool& p = c.tier == 0 ? x->dpool : x->hpool;
+        return p.segs[c.seg].base + c.off * p.block_bytes;
+    };
+    auto run_phase = [&]() {       // wait for the copies, commit the moves, release the sources
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        for (const Move& m : moves) {
+            if (e == hipSuccess) {
+                x->loc[m.l] = m.to;
+                pool_release(m.from.tier == 0 ? x->dpool : x->hpool, m.from.seg, m.from.off, (size_t)x->nblk[m.l]);
+            } else {
+                pool_release(m.to.tier == 0 ? x->dpool : x->hpool, m.to.seg, m.to.off, (size_t)x->nblk[m.l]);
+            }
+        }
+        moves.clear();
+    };
+    auto move_list = [&](int32_t l, int to_tier, int exclude, bool may_grow) -> bool {
+        const size_t nb = (size_t)x->nblk[l];
+        Loc from = x->loc[l], to;
+        to.tier = (int8_t)to_tier;
+        if (!nb) { x->loc[l].tier = (int8_t)to_tier; return true; }
+        if (!pool_alloc(to_tier == 0 ? x->dpool : x->hpool, nb, to.seg, to.off, may_grow, exclude)) return false;
+        if (e == hipSuccess) e = hipMemcpyAsync(addr(to), addr(from), nb * x->block_bytes, hipMemcpyDefault, 0);
+        const int64_t by = (int64_t)(nb * x->block_bytes);
+        if (from.tier == 0 && to_tier == 1) x->moved_d2h += by;
+        else if (from.tier == 1 && to_tier == 0) x->moved_h2d += by;
+        else x->moved_d2d += by;
+        moves.push_back({l, from, to});
+        return true;
+    };
+
+    // 2. evictions: HBM -> pinned host
+    for (int32_t l : evict)
+        if (!move_list(l, 1, -1, true)) { err = fail(IVF_ERR_OOM_HOST, "out of pinned host memory while evicting list %d", l); break; }
+    run_phase();
+
+    // 3. compaction of the HBM pool: empty the least-filled segments into the holes of the
+    //    others (device-to-device copies) and give their memory back
+    if (!err && e == hipSuccess && !evict.empty()) {
+        std::vector<std::vector<int32_t>> in_seg(x->dpool.segs.size());
+        for (int64_t l = 0; l < nlist; ++l)
+            if (x->loc[l].tier == 0 && x->loc[l].seg >= 0) in_seg[x->loc[l].seg].push_back((int32_t)l);
+        std::vector<int> segs;
+        for (size_t i = 0; i < x->dpool.segs.size(); ++i)
+            if (x->dpool.segs[i].base) segs.push_back((int)i);
+        std::sort(segs.begin(), segs.end(), [&](int a, int b) { return x->dpool.segs[a].used < x->dpool.segs[b].used; });
+        for (int sidx : segs) {
+            Seg& g = x->dpool.segs[sidx];
+            if (g.used == 0) continue;
+            size_t free_elsewhere = 0;
+            for (size_t i = 0; i < x->dpool.segs.size(); ++i)
+                if ((int)i != sidx && x->dpool.segs[i].base) free_elsewhere += x->dpool.segs[i].blocks - x->dpool.segs[i].used;
+            if (free_elsewhere < g.used) break;        // segments are visited least-filled first
+            bool ok = true;
+            const size_t first = moves.size();
+            for (int32_t l : in_seg[sidx])
+                if (!move_list(l, 0, sidx, false)) { ok = false; break; }
+            if (!ok) {                                   // holes too small: leave this segment alone
+                for (size_t i = first; i < moves.size(); ++i) {
+                    pool_release(x->dpool, moves[i].to.seg, moves[i].to.off, (size_t)x->nblk[moves[i].l]);
+                    x->moved_d2d -= (int64_t)((size_t)x->nblk[moves[i].l] * x->block_bytes);
+                }
+                // copies already queued for them only wrote into holes that stay free
+                moves.resize(first);
+                continue;
+            }
+            run_phase();
+            for (int32_t l : in_seg[sidx]) in_seg[x->loc[l].seg].push_back(l);
+            in_seg[sidx].clear();
+            if (e != hipSuccess) break;
+        }
+        pool_drop_empty(x->dpool);
+    }
+
+    // 4. loads: pinned host -> HBM
+    if (!err && e == hipSuccess) {
+        for (int32_t l : load)
+            if (!move_list(l, 0, -1, true)) { err = fail(IVF_ERR_OOM_DEVICE, "out of device memory while loading list %d", l); break; }
+        run_phase();
+        pool_drop_empty(x->hpool);
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        if (nd) (void)hipFree(nd);
-        if (nh) (void)hipHostFree(nh);
-        return fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(e));
+        err = fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(e));
     }
-    // empty lists keep a non-null device address so that they count as resident
-    for (int64_t l = 0; l < nlist; ++l)
-        if (res[l] && !ndp[l]) ndp[l] = nd ? nd : reinterpret_cast<const char*>(x->d_centroids);
-    dfree(x->d_arena);
-    if (x->h_arena) (void)hipHostFree(x->h_arena);
-    x->d_arena = nd; x->d_arena_bytes = new_dev;
-    x->h_arena = nh; x->h_arena_bytes = new_host;
-    x->dev_ptr.swap(ndp);
-    x->host_ptr.swap(nhp);
+    refresh_list_ptrs(x);
+    nres = 0;
+    for (int64_t l = 0; l < nlist; ++l) nres += x->loc[l].tier == 0;
     x->resident_lists = nres;
     if ((rc = upload_list_ptr_table(x))) return rc;
+    if (err) return err;
     if (nres < nlist) {
-        if ((rc = ensure_staging(x))) return rc;
+        if (!x->opt_host_direct && (rc = ensure_staging(x))) return rc;
     } else {
         free_staging(x);
     }
@@ -871,7 +1057,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
                        s.pair_start, cursor, s.pair_flat);
     hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
                        x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
-                       s.pair_flat, s.pair_of_probe, s.items);
+                       s.pair_flat, s.pair_of_probe, s.items, x->d_hits);
     mark();   // 3
     if (x->resident_lists > 0 || x->opt_host_direct) {
         const int mode = (int)x->opt_scan_mode;
@@ -916,6 +1102,11 @@ int ivf_get_info(ivf_index* x, ivf_info* out) {
     out->host_list_bytes = out->index_bytes - dev;
     out->resident_lists = x->resident_lists;
     out->scratch_bytes = (int64_t)x->sc.bytes;
+    out->device_pool_bytes = (int64_t)(x->dpool.allocated_blocks() * x->block_bytes);
+    out->host_pool_bytes = (int64_t)(x->hpool.allocated_blocks() * x->block_bytes);
+    out->moved_h2d_bytes = x->moved_h2d;
+    out->moved_d2h_bytes = x->moved_d2h;
+    out->moved_d2d_bytes = x->moved_d2d;
     return 0;
 }
 
@@ -1075,6 +1266,8 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
         }
     }
     else if (n == "nside" && value >= 1 && value <= kMaxSide) x->opt_nside = value;
+    else if (n == "residency_policy" && (value == 0 || value == 1)) x->opt_policy = value;   // 0 largest, 1 most probed
+    else if (n == "segment_mb" && value >= 1 && value <= 65536) x->opt_segment_mb = value;  // next upload
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
     else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);

@@ -167,11 +167,13 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
                        const uint32_t* __restrict__ pair_start,
                        const uint32_t* __restrict__ sblk_start,
                        const uint32_t* __restrict__ item_start, uint32_t* __restrict__ pair_flat,
-                       uint32_t* __restrict__ pair_of_probe, ScanItem* __restrict__ items) {
+                       uint32_t* __restrict__ pair_of_probe, ScanItem* __restrict__ items,
+                       uint32_t* __restrict__ hits) {
     int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
     const unsigned cnt = (unsigned)hist[l] & kHistCountMask;
     if (!cnt) return;
+    hits[l] += cnt;                  // lifetime probe count of the list (residency policy)
     const uint32_t ps = pair_start[l];
     uint32_t* seg = pair_flat + ps;
     for (unsigned i = 1; i < cnt; ++i) {        // insertion sort: segments are tiny

@@ -260,16 +260,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_scan(
 // grid.x = list within the piece, grid.y = block within the list.
 __global__ __launch_bounds__(256) void k_relayout(const char* __restrict__ src_rows,
                                                   const int64_t* __restrict__ offsets,
-                                                  const int64_t* __restrict__ blk_off,
-                                                  int64_t list_begin, int row_bytes,
-                                                  char* __restrict__ arena) {
+                                                  const void* const* __restrict__ list_ptr,
+                                                  int64_t list_begin, int row_bytes) {
     const int64_t l = list_begin + blockIdx.x;
     const int64_t len = offsets[l + 1] - offsets[l];
     const int64_t b = blockIdx.y;
     if (b * kLanes >= len) return;
     const int64_t row0 = offsets[l] - offsets[list_begin] + b * kLanes;
     const int nchunk = row_bytes / 16;
-    u4* dst = reinterpret_cast<u4*>(arena + (size_t)(blk_off[l] + b) * kLanes * (size_t)row_bytes);
+    u4* dst = reinterpret_cast<u4*>(static_cast<char*>(const_cast<void*>(list_ptr[l])) + (size_t)b * kLanes * (size_t)row_bytes);
     for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
         int c = u / kLanes, lane = u % kLanes;
         u4 v = {0u, 0u, 0u, 0u};

@@ -41,7 +41,10 @@ class Info(C.Structure):
     _fields_ = [("d", C.c_int32), ("dtype", C.c_int32), ("nlist", C.c_int64), ("n", C.c_int64),
                 ("max_list_len", C.c_int64), ("index_bytes", C.c_int64),
                 ("device_list_bytes", C.c_int64), ("host_list_bytes", C.c_int64),
-                ("resident_lists", C.c_int64), ("scratch_bytes", C.c_int64)]
+                ("resident_lists", C.c_int64), ("scratch_bytes", C.c_int64),
+                ("device_pool_bytes", C.c_int64), ("host_pool_bytes", C.c_int64),
+                ("moved_h2d_bytes", C.c_int64), ("moved_d2h_bytes", C.c_int64),
+                ("moved_d2d_bytes", C.c_int64)]
 
 
 class SearchStats(C.Structure):

@@ -28,7 +28,7 @@ def test_header_symbols_are_all_exported_and_bound():
 
 
 def test_info_and_stats_structs_match_header_layout():
-    assert C.sizeof(ivf.Info) == 8 + 8 * 8
+    assert C.sizeof(ivf.Info) == 8 + 13 * 8
     assert C.sizeof(ivf.SearchStats) == 7 * 8
 
 

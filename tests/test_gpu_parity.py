@@ -261,6 +261,81 @@ def test_results_do_not_depend_on_placement(c1):
         idx.set_device_budget(2**62)
 
 
+def test_budget_changes_move_only_the_difference_and_give_memory_back(c1):
+    """Repeated budget changes between batches (the paper changes the number of resident
+    partitions at run time, Sections 4.2 and 5): only lists that change tier cross PCIe,
+    the HBM pool shrinks with the budget, results never change."""
+    w, h, idx = c1
+    q = W.queries(w, batch=8)
+    ref = gpu_search(idx, q, w.nprobe, w.k)
+    lens = np.diff(h.offsets)
+    nblk = (lens + 63) // 64
+    bb = 64 * w.d * 4
+    order = np.lexsort((np.arange(w.nlist), -lens))
+    total = int(nblk.sum()) * bb
+    seg = 64 << 20                                   # C1 is smaller than 16 segments of 64 MiB
+
+    def resident_set(budget):
+        used, keep = 0, set()
+        for l in order:
+            b = int(nblk[l]) * bb
+            if used + b > budget:
+                break
+            used += b
+            keep.add(int(l))
+        return keep
+
+    cur = set(range(w.nlist))
+    try:
+        for frac in (0.25, 0.30, 0.10, 0.0, 0.5, 1.0):
+            budget = int(total * frac)
+            want = resident_set(budget)
+            say(f"C1 budget -> {frac:.2f}: {len(want)} lists resident")
+            idx.set_device_budget(budget)
+            info = idx.info()
+            assert info.resident_lists == len(want)
+            out_b = sum(int(nblk[l]) * bb for l in cur - want)
+            in_b = sum(int(nblk[l]) * bb for l in want - cur)
+            assert info.moved_d2h_bytes == out_b and info.moved_h2d_bytes == in_b
+            res_b = sum(int(nblk[l]) * bb for l in want)
+            assert info.device_list_bytes == res_b and info.host_list_bytes == total - res_b
+            assert res_b <= info.device_pool_bytes <= res_b + 2 * seg
+            assert total - res_b <= info.host_pool_bytes <= total - res_b + 2 * seg
+            got = gpu_search(idx, q, w.nprobe, w.k)
+            assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+            for l in (0, 77, 255):
+                vec, ids = idx.read_list(l, w.d, ivf.IVF_FP32)
+                assert np.array_equal(vec, h.vectors[h.offsets[l]:h.offsets[l + 1]])
+                assert np.array_equal(ids, h.ids[h.offsets[l]:h.offsets[l + 1]])
+            cur = want
+    finally:
+        idx.set_device_budget(2**62)
+
+
+def test_most_probed_lists_stay_resident_under_the_hot_policy(c1):
+    w, h, _ = c1
+    idx = upload_host_index(h)                      # fresh probe counts
+    q = W.queries(w, batch=9)
+    ref = gpu_search(idx, q, w.nprobe, w.k)
+    probed = np.unique(ref[2])
+    nblk = (np.diff(h.offsets) + 63) // 64
+    bb = 64 * w.d * 4
+    budget = int(sum(int(nblk[l]) for l in probed)) * bb
+    say("C1 budget = size of the probed lists, ranked by length")
+    idx.set_device_budget(budget)
+    got = gpu_search(idx, q, w.nprobe, w.k)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    assert idx.last_search_stats().scan_bytes_streamed > 0
+    say("C1 same budget, ranked by probe count")
+    idx.set_option("residency_policy", 1)
+    idx.set_device_budget(budget)
+    got = gpu_search(idx, q, w.nprobe, w.k)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    st = idx.last_search_stats()
+    assert st.scan_bytes_streamed == 0 and idx.info().resident_lists == len(probed)
+    idx.close()
+
+
 def test_scan_launch_options_agree(c1):
     w, h, idx = c1
     q = W.queries(w, batch=5)
