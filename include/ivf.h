@@ -254,6 +254,46 @@ int ivf_sched_single_batch_is_best(double c, int64_t k);
 int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, int m, double mean_arrival,
                      int64_t *best_batch, double *best_latency);
 
+/* ---- retrieval worker: request queue -> batches -> context queue ----
+ *
+ * The retrieval half of the decoupled pipeline (paper Section 4.1): requests are put in
+ * a retrieval queue; a worker thread forms batches on its own, runs ivf_search on a
+ * stream of its own and puts each request's result in a context queue, from which the
+ * consumer (the generation side) takes it.  With a backlog of n requests the worker
+ * serves them in batches of the size the backlog-aware rule picks (Section 4.4;
+ * candidates 1, 2, 4, ... max_batch; T(B) fitted to the worker's own batch timings; the
+ * whole backlog up to max_batch until two batch sizes have been timed).
+ *
+ * While a worker runs it is the only caller of ivf_search on its index (no other
+ * search, upload or budget change on that index until ivf_worker_stop).  Queries and
+ * results are HOST buffers; submit and wait may be called from any threads.
+ */
+typedef struct ivf_worker ivf_worker;
+
+typedef struct {
+    int64_t requests_submitted, requests_done, batches, largest_batch;
+    int64_t queued;            /* waiting in the retrieval queue right now */
+    int64_t results_waiting;   /* finished, not yet taken from the context queue */
+    double fit_a_ms, fit_c;    /* last fit of T(B) = a * B^c (0 until there is one) */
+} ivf_worker_stats;
+
+/* Starts the worker thread on the current HIP device for searches with (nprobe, k). */
+int ivf_worker_start(ivf_index *idx, int nprobe, int k, int max_batch, ivf_worker **out);
+
+/* Copies one query [d] fp32 from HOST memory into the retrieval queue; *ticket names it. */
+int ivf_worker_submit(ivf_worker *w, const float *query, uint64_t *ticket);
+
+/* Takes the result of `ticket` out of the context queue into HOST buffers ids[k],
+   scores[k].  timeout_ms < 0 waits; otherwise returns 1 if it is not ready in time.
+   Every ticket can be taken exactly once (a second take returns IVF_ERR_INVALID). */
+int ivf_worker_wait(ivf_worker *w, uint64_t ticket, int64_t *out_ids, float *out_scores, int timeout_ms);
+
+int ivf_worker_get_stats(ivf_worker *w, ivf_worker_stats *out);
+
+/* Serves what is still queued, stops the thread and frees the worker (results not
+   taken are dropped).  Returns the worker's error code if it had failed. */
+int ivf_worker_stop(ivf_worker *w);
+
 #ifdef __cplusplus
 }
 #endif

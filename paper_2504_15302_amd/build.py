@@ -32,7 +32,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(os.path.dirname(HERE), "include", "ivf.h"))
     objs = []
-    for name in ("ivf_sort", "ivf_api"):
+    for name in ("ivf_sort", "ivf_api", "ivf_worker"):
         src = os.path.join(CSRC, name + ".hip")
         obj = os.path.join(OBJ_DIR, name + ".o")
         deps = [src] + (headers if name != "ivf_sort" else [])
@@ -53,7 +53,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     objs.append(sched_obj)
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

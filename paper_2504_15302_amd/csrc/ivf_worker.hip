@@ -1,0 +1,228 @@
+// Retrieval worker: the retrieval half of a decoupled retrieve-then-generate pipeline
+// (paper Section 4.1: requests wait in a retrieval queue, a retrieval worker forms
+// batches on its own and puts the retrieved contexts into the queue of the generation
+// worker).  One host thread drains a request queue into ivf_search batches on its own
+// stream; finished results wait in a context queue until the consumer takes them.  The
+// batch size for the current backlog comes from the backlog-aware rule (Section 4.4),
+// fed by the worker's own timings.  Exports the ivf_worker_* part of include/ivf.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <condition_variable>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <thread>
+#include <unordered_map>
+#include <unordered_set>
+#include <vector>
+
+#include "../../include/ivf.h"
+
+namespace {
+
+struct Request {
+    uint64_t ticket;
+    std::vector<float> q;
+};
+struct Result {
+    std::vector<int64_t> ids;
+    std::vector<float> scores;
+};
+
+}  // namespace
+
+struct ivf_worker {
+    ivf_index* idx = nullptr;
+    int device = 0, d = 0, nprobe = 0, k = 0, max_batch = 0;
+    std::thread th;
+    std::mutex mu;
+    std::condition_variable cv_req, cv_res;
+    std::deque<Request> requests;                       // retrieval queue
+    std::unordered_map<uint64_t, Result> done;          // context queue
+    std::unordered_set<uint64_t> outstanding;           // submitted and not yet taken
+    uint64_t next_ticket = 1;
+    bool stopping = false, failed = false;
+    int fail_code = 0;
+    // per batch size (power of two index): smoothed time of one search, in ms
+    std::vector<double> t_ms;
+    std::vector<int> t_n;
+    ivf_worker_stats st = {};
+};
+
+namespace {
+
+void worker_loop(ivf_worker* w) {
+    if (hipSetDevice(w->device) != hipSuccess) { std::lock_guard<std::mutex> g(w->mu); w->failed = true; w->fail_code = IVF_ERR_HIP; w->cv_res.notify_all(); return; }
+    hipStream_t st = nullptr;
+    float *hq = nullptr, *dq = nullptr, *hs = nullptr, *ds = nullptr;
+    int64_t *hi = nullptr, *di = nullptr;
+    const size_t B = (size_t)w->max_batch;
+    bool ok = hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&hq), B * w->d * sizeof(float)) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&hs), B * w->k * sizeof(float)) == hipSuccess &&
+              hipHostMalloc(reinterpret_cast<void**>(&hi), B * w->k * sizeof(int64_t)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void**>(&dq), B * w->d * sizeof(float)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void**>(&ds), B * w->k * sizeof(float)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void**>(&di), B * w->k * sizeof(int64_t)) == hipSuccess;
+    std::vector<int64_t> cands;
+    for (int b = 1; b <= w->max_batch; b <<= 1) cands.push_back(b);
+    if (cands.back() != w->max_batch) cands.push_back(w->max_batch);
+    std::vector<Request> batch;
+    while (ok) {
+        batch.clear();
+        {
+            std::unique_lock<std::mutex> lk(w->mu);
+            w->cv_req.wait(lk, [&] { return w->stopping || !w->requests.empty(); });
+            if (w->requests.empty()) break;                    // stopping and drained
+            const int64_t n = (int64_t)w->requests.size();
+            // batch size for this backlog: the backlog-aware rule once two batch sizes have
+            // been timed, the whole backlog (up to max_batch) before that
+            int64_t take = std::min<int64_t>(n, w->max_batch);
+            std::vector<double> bs, ts;
+            for (size_t i = 0; i < cands.size(); ++i)
+                if (w->t_n[i] > 0) { bs.push_back((double)cands[i]); ts.push_back(w->t_ms[i]); }
+            if (bs.size() >= 2) {
+                double a = 0, c = 0;
+                if (ivf_sched_fit(bs.data(), ts.data(), (int)bs.size(), &a, &c) == 0 && a > 0 && c >= 0) {
+                    int64_t best = take;
+                    if (ivf_sched_choose(a, c, n, cands.data(), (int)cands.size(), 0.0, &best, nullptr) == 0)
+                        take = std::min<int64_t>(std::min<int64_t>(best, n), w->max_batch);
+                    w->st.fit_a_ms = a;
+                    w->st.fit_c = c;
+                }
+            }
+            for (int64_t i = 0; i < take; ++i) {
+                batch.push_back(std::move(w->requests.front()));
+                w->requests.pop_front();
+            }
+        }
+        const size_t nb = batch.size();
+        for (size_t i = 0; i < nb; ++i) std::memcpy(hq + i * w->d, batch[i].q.data(), sizeof(float) * w->d);
+        const auto t0 = std::chrono::steady_clock::now();
+        int rc = 0;
+        if (hipMemcpyAsync(dq, hq, nb * w->d * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess) rc = IVF_ERR_HIP;
+        if (!rc) rc = ivf_search(w->idx, dq, (int64_t)nb, w->nprobe, w->k, di, ds, st);
+        if (!rc && (hipMemcpyAsync(hi, di, nb * w->k * sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+                    hipMemcpyAsync(hs, ds, nb * w->k * sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess ||
+                    hipStreamSynchronize(st) != hipSuccess))
+            rc = IVF_ERR_HIP;
+        const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        std::lock_guard<std::mutex> g(w->mu);
+        if (rc) {
+            w->failed = true;
+            w->fail_code = rc;
+            w->cv_res.notify_all();
+            break;
+        }
+        for (size_t i = 0; i < nb; ++i) {
+            Result r;
+            r.ids.assign(hi + i * w->k, hi + (i + 1) * w->k);
+            r.scores.assign(hs + i * w->k, hs + (i + 1) * w->k);
+            w->done.emplace(batch[i].ticket, std::move(r));
+        }
+        // time of a batch of this size, filed under the smallest candidate that holds it
+        size_t slot = 0;
+        while (slot + 1 < cands.size() && (int64_t)nb > cands[slot]) ++slot;
+        w->t_ms[slot] = w->t_n[slot] ? 0.75 * w->t_ms[slot] + 0.25 * ms : ms;
+        w->t_n[slot] += 1;
+        w->st.batches += 1;
+        w->st.requests_done += (int64_t)nb;
+        w->st.largest_batch = std::max<int64_t>(w->st.largest_batch, (int64_t)nb);
+        w->cv_res.notify_all();
+    }
+    if (!ok) {
+        std::lock_guard<std::mutex> g(w->mu);
+        w->failed = true;
+        w->fail_code = IVF_ERR_OOM_DEVICE;
+        w->cv_res.notify_all();
+    }
+    (void)hipGetLastError();
+    if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
+    if (hq) (void)hipHostFree(hq);
+    if (hs) (void)hipHostFree(hs);
+    if (hi) (void)hipHostFree(hi);
+    if (dq) (void)hipFree(dq);
+    if (ds) (void)hipFree(ds);
+    if (di) (void)hipFree(di);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ivf_worker_start(ivf_index* idx, int nprobe, int k, int max_batch, ivf_worker** out) {
+    if (!out) return IVF_ERR_INVALID;
+    *out = nullptr;
+    ivf_info info;
+    if (!idx || ivf_get_info(idx, &info) != 0) return IVF_ERR_INVALID;
+    if (nprobe < 1 || k < 1 || k > 1024 || max_batch < 1 || max_batch > 65535) return IVF_ERR_INVALID;
+    ivf_worker* w = new (std::nothrow) ivf_worker();
+    if (!w) return IVF_ERR_OOM_HOST;
+    w->idx = idx; w->d = info.d; w->nprobe = nprobe; w->k = k; w->max_batch = max_batch;
+    if (hipGetDevice(&w->device) != hipSuccess) { delete w; return IVF_ERR_HIP; }
+    int nc = 0;
+    for (int b = 1; b <= max_batch; b <<= 1) ++nc;
+    w->t_ms.assign((size_t)nc + 1, 0.0);
+    w->t_n.assign((size_t)nc + 1, 0);
+    w->th = std::thread(worker_loop, w);
+    *out = w;
+    return 0;
+}
+
+int ivf_worker_submit(ivf_worker* w, const float* query, uint64_t* ticket) {
+    if (!w || !query || !ticket) return IVF_ERR_INVALID;
+    Request r;
+    r.q.assign(query, query + w->d);
+    std::lock_guard<std::mutex> g(w->mu);
+    if (w->stopping) return IVF_ERR_INVALID;
+    if (w->failed) return w->fail_code;
+    r.ticket = w->next_ticket++;
+    *ticket = r.ticket;
+    w->outstanding.insert(r.ticket);
+    w->requests.push_back(std::move(r));
+    w->st.requests_submitted += 1;
+    w->cv_req.notify_one();
+    return 0;
+}
+
+int ivf_worker_wait(ivf_worker* w, uint64_t ticket, int64_t* out_ids, float* out_scores, int timeout_ms) {
+    if (!w || !out_ids || !out_scores) return IVF_ERR_INVALID;
+    std::unique_lock<std::mutex> lk(w->mu);
+    if (!w->outstanding.count(ticket)) return IVF_ERR_INVALID;     // never issued, or taken before
+    auto ready = [&] { return w->failed || w->done.count(ticket) != 0; };
+    if (timeout_ms < 0) w->cv_res.wait(lk, ready);
+    else if (!w->cv_res.wait_for(lk, std::chrono::milliseconds(timeout_ms), ready)) return 1;   // not ready yet
+    auto it = w->done.find(ticket);
+    if (it == w->done.end()) return w->failed ? w->fail_code : IVF_ERR_INVALID;   // failed, or taken before
+    std::memcpy(out_ids, it->second.ids.data(), sizeof(int64_t) * w->k);
+    std::memcpy(out_scores, it->second.scores.data(), sizeof(float) * w->k);
+    w->done.erase(it);
+    w->outstanding.erase(ticket);
+    return 0;
+}
+
+int ivf_worker_get_stats(ivf_worker* w, ivf_worker_stats* out) {
+    if (!w || !out) return IVF_ERR_INVALID;
+    std::lock_guard<std::mutex> g(w->mu);
+    *out = w->st;
+    out->queued = (int64_t)w->requests.size();
+    out->results_waiting = (int64_t)w->done.size();
+    return 0;
+}
+
+int ivf_worker_stop(ivf_worker* w) {
+    if (!w) return IVF_ERR_INVALID;
+    {
+        std::lock_guard<std::mutex> g(w->mu);
+        w->stopping = true;
+        w->cv_req.notify_all();
+    }
+    if (w->th.joinable()) w->th.join();
+    const int rc = w->failed ? w->fail_code : 0;
+    delete w;
+    return rc;
+}
+
+}  // extern "C"

@@ -28,6 +28,7 @@ EXPORTS = (
     "ivf_set_option", "ivf_debug_copy", "ivf_debug_read",
     "ivf_sched_fit", "ivf_sched_batch_time", "ivf_sched_avg_latency", "ivf_sched_single_batch_is_best",
     "ivf_sched_choose",
+    "ivf_worker_start", "ivf_worker_submit", "ivf_worker_wait", "ivf_worker_get_stats", "ivf_worker_stop",
 )
 
 
@@ -51,6 +52,12 @@ class SearchStats(C.Structure):
     _fields_ = [("unique_lists", C.c_int64), ("pairs", C.c_int64), ("scanned_vectors", C.c_int64),
                 ("scan_bytes", C.c_int64), ("scan_bytes_resident", C.c_int64),
                 ("scan_bytes_streamed", C.c_int64), ("scan_items", C.c_int64)]
+
+
+class WorkerStats(C.Structure):
+    _fields_ = [("requests_submitted", C.c_int64), ("requests_done", C.c_int64), ("batches", C.c_int64),
+                ("largest_batch", C.c_int64), ("queued", C.c_int64), ("results_waiting", C.c_int64),
+                ("fit_a_ms", C.c_double), ("fit_c", C.c_double)]
 
 
 _lib = None
@@ -98,6 +105,11 @@ def load_library() -> C.CDLL:
     lib.ivf_sched_avg_latency.argtypes = [dbl, dbl, i64, i64, dbl, pd]
     lib.ivf_sched_single_batch_is_best.argtypes = [dbl, i64]
     lib.ivf_sched_choose.argtypes = [dbl, dbl, i64, pi64, i32, dbl, pi64, pd]
+    lib.ivf_worker_start.argtypes = [vp, i32, i32, i32, C.POINTER(vp)]
+    lib.ivf_worker_submit.argtypes = [vp, vp, C.POINTER(C.c_uint64)]
+    lib.ivf_worker_wait.argtypes = [vp, C.c_uint64, vp, vp, i32]
+    lib.ivf_worker_get_stats.argtypes = [vp, C.POINTER(WorkerStats)]
+    lib.ivf_worker_stop.argtypes = [vp]
     for name in EXPORTS:
         if name not in ("ivf_index_destroy", "ivf_last_error", "ivf_sched_batch_time"):
             getattr(lib, name).restype = C.c_int
@@ -294,4 +306,50 @@ def sched_choose(a: float, c: float, n: int, candidates, mean_arrival: float = 0
 
 def _check_plain(rc: int):
     if rc != 0:
-        raise IvfError(rc, "invalid argument to an ivf_sched_* function")
+        raise IvfError(rc, "ivf_sched_* / ivf_worker_* call failed (invalid argument, or the worker has failed)")
+
+
+class Worker:
+    """Owner of one `ivf_worker*`: submit host queries, take results by ticket."""
+
+    def __init__(self, index: Index, nprobe: int, k: int, max_batch: int):
+        self._lib = load_library()
+        self._index = index          # keeps the index alive
+        self.k = k
+        self.d = index.info().d
+        h = C.c_void_p()
+        _check_plain(self._lib.ivf_worker_start(index._h, nprobe, k, max_batch, C.byref(h)))
+        self._h = h
+
+    def submit(self, query: np.ndarray) -> int:
+        q = np.ascontiguousarray(query, dtype=np.float32)
+        assert q.shape == (self.d,)
+        t = C.c_uint64()
+        _check_plain(self._lib.ivf_worker_submit(self._h, q.ctypes.data, C.byref(t)))
+        return t.value
+
+    def wait(self, ticket: int, timeout_ms: int = -1):
+        """(ids[k], scores[k]) or None if not ready within the timeout."""
+        ids = np.empty(self.k, dtype=np.int64)
+        scores = np.empty(self.k, dtype=np.float32)
+        rc = self._lib.ivf_worker_wait(self._h, ticket, ids.ctypes.data, scores.ctypes.data, timeout_ms)
+        if rc == 1:
+            return None
+        _check_plain(rc)
+        return ids, scores
+
+    def stats(self) -> WorkerStats:
+        out = WorkerStats()
+        _check_plain(self._lib.ivf_worker_get_stats(self._h, C.byref(out)))
+        return out
+
+    def stop(self):
+        if getattr(self, "_h", None):
+            h, self._h = self._h, None
+            _check_plain(self._lib.ivf_worker_stop(h))
+
+    def __del__(self):
+        try:
+            self.stop()
+        except Exception:
+            pass

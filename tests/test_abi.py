@@ -30,6 +30,7 @@ def test_header_symbols_are_all_exported_and_bound():
 def test_info_and_stats_structs_match_header_layout():
     assert C.sizeof(ivf.Info) == 8 + 13 * 8
     assert C.sizeof(ivf.SearchStats) == 7 * 8
+    assert C.sizeof(ivf.WorkerStats) == 8 * 8
 
 
 def test_null_arguments_return_error_codes_without_a_gpu():
@@ -40,6 +41,11 @@ def test_null_arguments_return_error_codes_without_a_gpu():
     assert lib.ivf_set_device_budget(None, 0) == -1
     assert lib.ivf_index_upload_end(None) == -1
     assert lib.ivf_set_option(None, b"scan_mode", 0) == -1
+    assert lib.ivf_worker_start(None, 1, 1, 1, None) == -1
+    assert lib.ivf_worker_submit(None, None, None) == -1
+    assert lib.ivf_worker_wait(None, 1, None, None, 0) == -1
+    assert lib.ivf_worker_get_stats(None, None) == -1
+    assert lib.ivf_worker_stop(None) == -1
     lib.ivf_index_destroy(None)   # allowed
 
 
