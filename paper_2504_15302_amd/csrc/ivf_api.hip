@@ -997,10 +997,23 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     if (nq > 65535) return fail(IVF_ERR_LIMIT, "nq above 65535");
     if ((uint64_t)nq * (uint64_t)nprobe >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "nq*nprobe above 2^31");
     if ((uint64_t)block_bound(x, nq, nprobe) >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "batch too large for one call");
+    {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev != x->device)
+            return fail(IVF_ERR_INVALID, "the index lives on HIP device %d but the current device is %d", x->device, dev);
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool offload = x->resident_lists < x->nlist && !x->opt_host_direct;
     if (offload && (rc = ensure_staging(x))) return rc;
-    if ((rc = ensure_scratch(x, nq, nprobe, offload))) return rc;
+    if ((rc = ensure_scratch(x, nq, nprobe, offload))) {
+        // a failed growth leaves some buffers freed: drop all of them so that the sizes on
+        // record match what exists (the next search allocates afresh); the error message stays
+        std::string msg = g_err;
+        (void)hipDeviceSynchronize();
+        free_scratch(x->sc);
+        g_err = msg;
+        return rc;
+    }
     Scratch& s = x->sc;
     const int nlist = (int)x->nlist;
     const int ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
