@@ -81,6 +81,61 @@ def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
             "seconds": t}
 
 
+def budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log):
+    """Times a change of residency between the placement at hand and a quarter of the lists
+    HBM-resident, both ways: with the blocking call, and in the background with searches
+    issued back to back meanwhile (each compared with the rows from before the change)."""
+    import numpy as np
+    import torch
+    lens = np.diff(lw.offsets)
+    order = np.lexsort((np.arange(w.nlist), -lens))
+    keep = order[: w.nlist // 4]
+    quarter = int(((lens[keep] + 63) // 64).sum()) * 64 * w.d * w.elem_bytes
+    start = idx.info().device_list_bytes
+    nb = len(q_dev)
+
+    def searches_per_s(n=8):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores)
+        torch.cuda.synchronize()
+        return n / (time.perf_counter() - t0)
+
+    out = {"quarter_budget_bytes": quarter, "start_device_bytes": int(start), "legs": []}
+    for mode in ("blocking", "background"):
+        for target, name in ((quarter, "shrink to a quarter of the lists"), (start, "grow back")):
+            steady_before = searches_per_s()
+            t0 = time.perf_counter()
+            n_search = 0
+            ok = True
+            if mode == "blocking":
+                idx.set_device_budget(target)
+            else:
+                idx.set_device_budget_async(target)
+                while idx.budget_progress()[2]:
+                    idx.search(q_dev[0], w.nprobe, w.k, out_ids, out_scores)
+                    torch.cuda.synchronize()
+                    n_search += 1
+                    if n_search % 16 == 1:
+                        ok = ok and np.array_equal(out_ids.cpu().numpy(), first[0]) and \
+                            np.array_equal(out_scores.cpu().numpy(), first[1])
+            dt = time.perf_counter() - t0
+            info = idx.info()
+            moved = info.moved_h2d_bytes + info.moved_d2h_bytes
+            leg = {"mode": mode, "change": name, "seconds": dt, "moved_pcie_GB": moved / 1e9,
+                   "moved_inside_hbm_GB": info.moved_d2d_bytes / 1e9,
+                   "pcie_GBps": moved / 1e9 / dt if dt > 0 else None,
+                   "device_pool_GB_after": info.device_pool_bytes / 1e9,
+                   "searches_per_s_before": steady_before}
+            if mode == "background":
+                leg.update({"searches_during": n_search, "searches_per_s_during": n_search / dt if dt > 0 else None,
+                            "rows_unchanged": bool(ok)})
+            log(f"budget change: {leg}")
+            out["legs"].append(leg)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +152,9 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time ivf_search at batch sizes 8..nq, fit T(B) = a*B^c and report the "
                          "backlog-aware batch-size choice (ivf_sched_*)")
+    ap.add_argument("--budget-change", action="store_true",
+                    help="also time a change of the device budget (to a quarter of the lists and back), "
+                         "blocking and in the background while searches go on")
     ap.add_argument("--read-ceiling-gib", type=int, default=24,
                     help="size of the plain streaming-read measurement (0 skips it)")
     args = ap.parse_args()
@@ -276,6 +334,8 @@ def main():
             "batch_sizes": sizes, "ms_per_search": times, "fit_a_ms": a, "fit_c": c,
             "queue": w.nq, "chosen_batch": best, "avg_latency_ms_from_queue_start": lat,
             "single_batch_beats_two": ivf_mod.sched_single_batch_is_best(c, 2)}
+    if args.budget_change:
+        result["budget_change"] = budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log)
     if args.cpu_seconds > 0:
         log("timing the CPU oracle on a sample of batch 0")
         result["cpu_baseline"] = cpu_baseline(lw, idx, q_host[0], first[0], first[1], w.nprobe, w.k, args.cpu_seconds)

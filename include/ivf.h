@@ -119,6 +119,35 @@ int ivf_index_upload_end(ivf_index *idx);
 int ivf_set_device_budget(ivf_index *idx, int64_t bytes);
 
 /*
+ * ivf_set_device_budget_async — the same change of residency, carried out in the
+ * background while searches go on (the paper adjusts the resident partitions lazily,
+ * during the retrieval phase, on a stream of its own and synchronises only when needed:
+ * Section 5).  The call waits for the searches issued so far, works out which lists change
+ * tier, issues the first copies on the library's move stream and returns.  Lists move in
+ * batches ("move_chunk_kb", default 65536; at most "move_inflight_kb", default 4194304,
+ * under way at once), in three phases: evictions (least valuable list first), compaction
+ * of the HBM pool, loads (most valuable first).  A list keeps being searched at its old
+ * place until its copy has landed and the updated address table has reached the device
+ * behind all earlier searches; the old place is released only after those searches have
+ * finished, so every search sees each list in exactly one valid place and results never
+ * depend on how far the change has got.  The change advances inside every ivf_search,
+ * ivf_budget_progress and ivf_budget_wait call (nothing runs on a thread of the
+ * library's own); freeing an emptied segment waits for the device.
+ *   ivf_budget_progress  non-blocking step; reports the lists (and their padded bytes) that
+ *                        still have to change tier and whether anything is outstanding
+ *                        (pointers may be NULL)
+ *   ivf_budget_wait      blocks until the change is complete
+ * A change that runs out of memory stops where it is (searches stay correct); progress
+ * and wait then return the error until the next budget call.  Calling either budget
+ * function during a change lets the copies under way finish, drops the rest and plans
+ * anew from the placement reached.  Like searches, these calls must not overlap other
+ * calls on the same index.
+ */
+int ivf_set_device_budget_async(ivf_index *idx, int64_t bytes);
+int ivf_budget_progress(ivf_index *idx, int64_t *pending_lists, int64_t *pending_bytes, int *busy);
+int ivf_budget_wait(ivf_index *idx);
+
+/*
  * ivf_search — batched top-k inner-product search.
  *   queries     [nq, d] fp32 row-major, DEVICE pointer
  *   nq          batch size (0 is allowed and does nothing)
@@ -156,7 +185,7 @@ typedef struct {
     int64_t scratch_bytes;      /* search scratch currently allocated */
     int64_t device_pool_bytes;  /* HBM held by the list pool (whole segments, >= device_list_bytes) */
     int64_t host_pool_bytes;    /* pinned host memory held by the list pool */
-    int64_t moved_h2d_bytes;    /* last ivf_set_device_budget: bytes copied host -> HBM, */
+    int64_t moved_h2d_bytes;    /* last budget change (so far, if under way): bytes copied host -> HBM, */
     int64_t moved_d2h_bytes;    /*   HBM -> host, */
     int64_t moved_d2d_bytes;    /*   and inside HBM while compacting the pool */
 } ivf_info;
@@ -265,7 +294,8 @@ int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, i
  * whole backlog up to max_batch until two batch sizes have been timed).
  *
  * While a worker runs it is the only caller of ivf_search on its index (no other
- * search, upload or budget change on that index until ivf_worker_stop).  Queries and
+ * search, upload or direct budget change on that index until ivf_worker_stop; budget changes
+ * go through ivf_worker_set_device_budget).  Queries and
  * results are HOST buffers; submit and wait may be called from any threads.
  */
 typedef struct ivf_worker ivf_worker;
@@ -275,6 +305,11 @@ typedef struct {
     int64_t queued;            /* waiting in the retrieval queue right now */
     int64_t results_waiting;   /* finished, not yet taken from the context queue */
     double fit_a_ms, fit_c;    /* last fit of T(B) = a * B^c (0 until there is one) */
+    int64_t budget_changes;    /* budget changes taken up by the worker so far */
+    int64_t budget_pending_lists;  /* lists that still have to change tier */
+    int64_t budget_busy;       /* 1 while a change is under way or asked for */
+    int64_t resident_lists;    /* as of the worker's last look */
+    int64_t budget_error;      /* error code of the last change, 0 if none */
 } ivf_worker_stats;
 
 /* Starts the worker thread on the current HIP device for searches with (nprobe, k). */
@@ -289,6 +324,14 @@ int ivf_worker_submit(ivf_worker *w, const float *query, uint64_t *ticket);
 int ivf_worker_wait(ivf_worker *w, uint64_t ticket, int64_t *out_ids, float *out_scores, int timeout_ms);
 
 int ivf_worker_get_stats(ivf_worker *w, ivf_worker_stats *out);
+
+/* Asks the worker to change the device budget of its index (the scheduler of the paper
+   changes the number of resident partitions while the pipeline runs, Sections 4.2 and 5).
+   Returns at once; the worker starts the change between two batches with
+   ivf_set_device_budget_async and carries it on while it serves requests (and while it is
+   idle), so retrieval never stops for it.  A second request before the first is taken up
+   replaces it.  Progress: the budget_* fields of ivf_worker_stats. */
+int ivf_worker_set_device_budget(ivf_worker *w, int64_t bytes);
 
 /* Serves what is still queued, stops the thread and frees the worker (results not
    taken are dropped).  Returns the worker's error code if it had failed. */

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <deque>
 #include <limits>
 #include <map>
 #include <new>
@@ -127,6 +128,28 @@ struct Loc {
     size_t off = 0;                  // in blocks
 };
 
+// A change of the device budget is a sequence of list moves (HBM -> host, HBM -> HBM while
+// the pool is compacted, host -> HBM), copied in batches on a stream of their own while
+// searches go on.  A list keeps being read at its old place until its copy has landed and
+// the new address table has reached the device; the old place is released only after
+// every search that may still read it has finished.
+struct Move {
+    int32_t l = 0;
+    Loc from, to;
+    bool placed = false;             // destination already reserved (compaction)
+};
+struct MoveBatch {
+    hipEvent_t landed = nullptr;     // recorded on the move stream behind the batch's copies
+    std::vector<Move> moves;
+    size_t bytes = 0;
+};
+struct Limbo {
+    hipEvent_t after = nullptr;      // recorded behind the table update that retires the old places
+    const void** table = nullptr;    // pinned snapshot of the address table that the update copies
+    std::vector<Move> moves;         // their `from` places are released once `after` has completed
+};
+enum { kPhaseIdle = 0, kPhaseEvict = 1, kPhaseCompact = 2, kPhaseLoad = 3 };
+
 }  // namespace
 
 struct ivf_index {
@@ -155,6 +178,24 @@ struct ivf_index {
     uint32_t* d_hits = nullptr;        // per list: how often it has been probed (residency policy)
     int64_t resident_lists = 0;
     int64_t moved_h2d = 0, moved_d2h = 0, moved_d2d = 0;   // bytes moved by the last budget change
+    // budget change in progress
+    int phase = kPhaseIdle;
+    bool compact_wanted = false;
+    std::deque<Move> todo;             // moves of the current phase that have not been issued
+    std::deque<MoveBatch> inflight;    // issued, copy not yet known to have landed
+    std::deque<Limbo> limbo;           // landed and switched over, old places not yet released
+    std::vector<int32_t> to_load;      // lists to bring into HBM once evictions and compaction are over
+    std::vector<char> seg_skip;        // HBM segments that compaction could not empty
+    size_t inflight_bytes = 0;
+    int64_t pending_lists = 0, pending_bytes = 0;   // lists that still have to change tier
+    int move_rc = 0;                   // why the last change stopped early (0: it did not)
+    std::string move_msg;
+    hipStream_t move_stream = nullptr, patch_stream = nullptr;
+    hipEvent_t ev_search_end = nullptr;
+    bool search_end_recorded = false;
+    std::vector<hipEvent_t> spare_events;
+    std::vector<const void**> spare_tables;
+    const void** h_list_ptr = nullptr; // pinned host mirror of d_list_ptr
     // streaming of host-resident lists
     hipStream_t side[kMaxSide] = {};   // copy streams for host-resident lists (chunks alternate)
     char* stage[kMaxStage] = {};
@@ -177,7 +218,7 @@ struct ivf_index {
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
     int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
-            opt_nstage = 3;
+            opt_nstage = 3, opt_move_chunk_kb = 64 << 10, opt_move_inflight_kb = 4 << 20;
 };
 
 namespace {
@@ -262,18 +303,27 @@ void pool_drop_empty(Pool& p) {
         }
 }
 
-void refresh_list_ptrs(ivf_index* x) {
-    for (int64_t l = 0; l < x->nlist; ++l) {
-        const Loc& c = x->loc[l];
-        x->dev_ptr[l] = x->host_ptr[l] = nullptr;
-        if (c.seg < 0) {     // empty list: a non-null device address marks it resident
-            if (c.tier == 0) x->dev_ptr[l] = reinterpret_cast<const char*>(x->d_centroids);
-            continue;
-        }
+// Where list l is read from, as the host sees it (dev_ptr / host_ptr) and as the device
+// table will see it (h_list_ptr: a host-resident list has a null entry, or — when the scan
+// is to read pinned host memory directly — its host address tagged in bit 0).
+void set_list_entry(ivf_index* x, int64_t l) {
+    const Loc& c = x->loc[l];
+    x->dev_ptr[l] = x->host_ptr[l] = nullptr;
+    if (c.seg < 0) {         // empty list: a non-null device address marks it resident
+        if (c.tier == 0) x->dev_ptr[l] = reinterpret_cast<const char*>(x->d_centroids);
+    } else {
         const Pool& p = c.tier == 0 ? x->dpool : x->hpool;
         const char* a = p.segs[c.seg].base + c.off * p.block_bytes;
         (c.tier == 0 ? x->dev_ptr : x->host_ptr)[l] = a;
     }
+    const char* t = x->dev_ptr[l];
+    if (!t && x->host_ptr[l] && x->opt_host_direct)
+        t = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(x->host_ptr[l]) | 1u);
+    x->h_list_ptr[l] = t;
+}
+
+void refresh_list_ptrs(ivf_index* x) {
+    for (int64_t l = 0; l < x->nlist; ++l) set_list_entry(x, l);
 }
 
 void free_scratch(Scratch& s) {
@@ -297,10 +347,60 @@ void free_staging(ivf_index* x) {
     x->stage_bytes = 0;
 }
 
+hipEvent_t take_event(ivf_index* x) {
+    if (!x->spare_events.empty()) {
+        hipEvent_t e = x->spare_events.back();
+        x->spare_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return e;
+}
+
+const void** take_table(ivf_index* x) {
+    if (!x->spare_tables.empty()) {
+        const void** t = x->spare_tables.back();
+        x->spare_tables.pop_back();
+        return t;
+    }
+    const void** t = nullptr;
+    if (hipHostMalloc(reinterpret_cast<void**>(&t), sizeof(void*) * (size_t)x->nlist) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return t;
+}
+
+// Forgets a budget change in progress.  Only for an idle device whose pools are about to be
+// freed as a whole: nothing is released list by list.
+void moves_reset(ivf_index* x) {
+    for (MoveBatch& b : x->inflight)
+        if (b.landed) x->spare_events.push_back(b.landed);
+    for (Limbo& lb : x->limbo) {
+        if (lb.after) x->spare_events.push_back(lb.after);
+        if (lb.table) x->spare_tables.push_back(lb.table);
+    }
+    x->inflight.clear(); x->limbo.clear(); x->todo.clear(); x->to_load.clear(); x->seg_skip.clear();
+    for (const void** t : x->spare_tables) (void)hipHostFree(t);   // sized for the index that goes away
+    x->spare_tables.clear();
+    x->phase = kPhaseIdle;
+    x->inflight_bytes = 0;
+    x->pending_lists = x->pending_bytes = 0;
+    x->move_rc = 0;
+    x->move_msg.clear();
+    x->search_end_recorded = false;
+}
+
 void free_index_data(ivf_index* x) {
     dfree(x->d_centroids); dfree(x->d_offsets); dfree(x->d_len);
     dfree(x->d_nblk); dfree(x->d_list_ptr); dfree(x->d_ids_pos); dfree(x->d_id_sorted);
     dfree(x->d_rank_of_pos); dfree(x->d_hits);
+    if (x->h_list_ptr) { (void)hipHostFree(x->h_list_ptr); x->h_list_ptr = nullptr; }
+    moves_reset(x);
     pool_free_all(x->dpool);
     pool_free_all(x->hpool);
     free_staging(x);
@@ -323,14 +423,10 @@ int dalloc(T*& p, size_t count, size_t& total) {
     return 0;
 }
 
-// Device table of list addresses.  A host-resident list has a null entry, or — when the
-// scan is to read pinned host memory directly — its host address tagged in bit 0.
+// Device table of list addresses, copied from its host mirror (synchronous).
 int upload_list_ptr_table(ivf_index* x) {
-    std::vector<const char*> tab(x->dev_ptr);
-    if (x->opt_host_direct)
-        for (int64_t l = 0; l < x->nlist; ++l)
-            if (!tab[l] && x->host_ptr[l]) tab[l] = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(x->host_ptr[l]) | 1u);
-    HIP_TRY(hipMemcpy(x->d_list_ptr, tab.data(), sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice));
+    refresh_list_ptrs(x);
+    HIP_TRY(hipMemcpy(x->d_list_ptr, x->h_list_ptr, sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice));
     return 0;
 }
 
@@ -583,6 +679,281 @@ int check_ready(const ivf_index* x) {
     return 0;
 }
 
+
+// ---- budget changes as a background activity -------------------------------------------
+
+bool moves_active(const ivf_index* x) {
+    return x->phase != kPhaseIdle || !x->inflight.empty() || !x->limbo.empty();
+}
+
+char* loc_addr(ivf_index* x, const Loc& c) {
+    Pool& p = c.tier == 0 ? x->dpool : x->hpool;
+    return p.segs[c.seg].base + c.off * p.block_bytes;
+}
+
+void release_place(ivf_index* x, const Loc& c, int32_t l) {
+    pool_release(c.tier == 0 ? x->dpool : x->hpool, c.seg, c.off, (size_t)x->nblk[l]);
+}
+
+// Ends a change early: what has not been issued is dropped (reserved places are handed
+// back).  Copies already issued still land and are committed by moves_advance.
+void moves_stop(ivf_index* x, int rc, const std::string& msg) {
+    for (const Move& m : x->todo)
+        if (m.placed) release_place(x, m.to, m.l);
+    x->todo.clear();
+    x->to_load.clear();
+    x->phase = kPhaseIdle;
+    if (rc) {
+        x->move_rc = rc;
+        x->move_msg = msg;
+    }
+}
+
+// Sends the address table to the device behind the searches issued so far (the copy reads
+// a snapshot, so a later change of the mirror cannot reach an earlier search) and parks
+// the old places of `lb` until that has happened.
+int push_table(ivf_index* x, Limbo& lb) {
+    std::memcpy(lb.table, x->h_list_ptr, sizeof(void*) * (size_t)x->nlist);
+    if (x->search_end_recorded) HIP_TRY(hipStreamWaitEvent(x->patch_stream, x->ev_search_end, 0));
+    HIP_TRY(hipMemcpyAsync(x->d_list_ptr, lb.table, sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice, x->patch_stream));
+    HIP_TRY(hipEventRecord(lb.after, x->patch_stream));
+    x->limbo.push_back(std::move(lb));
+    return 0;
+}
+
+// Compaction of the HBM pool: picks the least-filled segment whose lists fit into the
+// holes of the other segments, reserves those holes and queues the device-to-device moves.
+bool compact_pick(ivf_index* x) {
+    Pool& p = x->dpool;
+    std::vector<int> segs;
+    size_t total_free = 0;
+    for (size_t i = 0; i < p.segs.size(); ++i) {
+        if (!p.segs[i].base) continue;
+        total_free += p.segs[i].blocks - p.segs[i].used;
+        if (p.segs[i].used > 0 && !(i < x->seg_skip.size() && x->seg_skip[i])) segs.push_back((int)i);
+    }
+    std::sort(segs.begin(), segs.end(), [&](int a, int b) { return p.segs[a].used < p.segs[b].used; });
+    for (int sidx : segs) {
+        const Seg& g = p.segs[sidx];
+        if (total_free - (g.blocks - g.used) < g.used) continue;
+        std::vector<int32_t> lists;
+        for (int64_t l = 0; l < x->nlist; ++l)
+            if (x->loc[l].tier == 0 && x->loc[l].seg == sidx) lists.push_back((int32_t)l);
+        if (lists.empty()) continue;
+        std::sort(lists.begin(), lists.end(), [&](int32_t a, int32_t b) {
+            return x->nblk[a] != x->nblk[b] ? x->nblk[a] > x->nblk[b] : a < b;     // large lists first: first fit packs better
+        });
+        std::vector<Move> mv;
+        bool ok = true;
+        for (int32_t l : lists) {
+            Move m;
+            m.l = l; m.from = x->loc[l]; m.to.tier = 0; m.placed = true;
+            if (!pool_alloc(p, (size_t)x->nblk[l], m.to.seg, m.to.off, false, sidx)) { ok = false; break; }
+            mv.push_back(m);
+        }
+        if (!ok) {                                   // holes too small: leave this segment alone
+            for (const Move& m : mv) release_place(x, m.to, m.l);
+            if ((size_t)sidx < x->seg_skip.size()) x->seg_skip[sidx] = 1;
+            continue;
+        }
+        for (const Move& m : mv) x->todo.push_back(m);
+        return true;
+    }
+    return false;
+}
+
+// The current phase has nothing left to issue, in flight or in limbo: go on to the next.
+void next_phase(ivf_index* x) {
+    if (x->phase == kPhaseEvict) {
+        x->phase = kPhaseCompact;
+        x->seg_skip.assign(x->dpool.segs.size(), 0);
+    }
+    if (x->phase == kPhaseCompact) {
+        pool_drop_empty(x->dpool);                   // the segment emptied last, if any
+        if (x->compact_wanted && compact_pick(x)) return;
+        x->phase = kPhaseLoad;
+        for (int32_t l : x->to_load) {
+            Move m;
+            m.l = l; m.from = x->loc[l]; m.to.tier = 0;
+            x->todo.push_back(m);
+        }
+        x->to_load.clear();
+        if (!x->todo.empty()) return;
+    }
+    pool_drop_empty(x->hpool);
+    x->phase = kPhaseIdle;
+}
+
+// One non-blocking step of the change in progress: releases old places whose readers are
+// done, switches over the lists whose copies have landed, issues further copies.
+int moves_advance(ivf_index* x) {
+    while (!x->limbo.empty()) {
+        Limbo& lb = x->limbo.front();
+        hipError_t q = hipEventQuery(lb.after);
+        if (q == hipErrorNotReady) { (void)hipGetLastError(); break; }
+        if (q != hipSuccess) { (void)hipGetLastError(); return fail(IVF_ERR_HIP, "list table update failed: %s", hipGetErrorString(q)); }
+        for (const Move& m : lb.moves) release_place(x, m.from, m.l);
+        x->spare_events.push_back(lb.after);
+        x->spare_tables.push_back(lb.table);
+        x->limbo.pop_front();
+    }
+    {
+        Limbo lb;
+        while (!x->inflight.empty()) {
+            MoveBatch& b = x->inflight.front();
+            hipError_t q = hipEventQuery(b.landed);
+            if (q == hipErrorNotReady) { (void)hipGetLastError(); break; }
+            if (q != hipSuccess) { (void)hipGetLastError(); return fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(q)); }
+            if (!lb.after) {
+                lb.after = take_event(x);
+                lb.table = take_table(x);
+                if (!lb.after || !lb.table) {
+                    if (lb.after) x->spare_events.push_back(lb.after);
+                    if (lb.table) x->spare_tables.push_back(lb.table);
+                    return fail(IVF_ERR_OOM_HOST, "no event or pinned table for a list table update");
+                }
+            }
+            for (const Move& m : b.moves) {
+                x->loc[m.l] = m.to;
+                set_list_entry(x, m.l);
+                const int64_t by = (int64_t)((size_t)x->nblk[m.l] * x->block_bytes);
+                if (m.from.tier == 0 && m.to.tier == 1) { x->moved_d2h += by; x->resident_lists -= 1; }
+                else if (m.from.tier == 1 && m.to.tier == 0) { x->moved_h2d += by; x->resident_lists += 1; }
+                else x->moved_d2d += by;
+                lb.moves.push_back(m);
+            }
+            x->inflight_bytes -= b.bytes;
+            x->spare_events.push_back(b.landed);
+            x->inflight.pop_front();
+        }
+        if (lb.after) {
+            int rc = push_table(x, lb);
+            if (rc) return rc;
+        }
+    }
+    const size_t chunk = (size_t)x->opt_move_chunk_kb << 10, cap = (size_t)x->opt_move_inflight_kb << 10;
+    while (x->phase != kPhaseIdle) {
+        if (x->todo.empty()) {
+            if (!x->inflight.empty() || !x->limbo.empty()) break;
+            next_phase(x);
+            continue;
+        }
+        if (x->inflight_bytes >= cap) break;
+        MoveBatch b;
+        b.landed = take_event(x);
+        if (!b.landed) { moves_stop(x, IVF_ERR_HIP, "no event for a batch of list copies"); break; }
+        while (!x->todo.empty() && b.bytes < chunk && x->inflight_bytes + b.bytes < cap) {
+            Move m = x->todo.front();
+            const size_t nb = (size_t)x->nblk[m.l];
+            if (!m.placed && !pool_alloc(m.to.tier == 0 ? x->dpool : x->hpool, nb, m.to.seg, m.to.off, true)) {
+                char msg[128];
+                std::snprintf(msg, sizeof msg, "out of %s memory while moving list %d", m.to.tier == 0 ? "device" : "pinned host", m.l);
+                moves_stop(x, m.to.tier == 0 ? IVF_ERR_OOM_DEVICE : IVF_ERR_OOM_HOST, msg);
+                break;
+            }
+            x->todo.pop_front();
+            hipError_t e = hipMemcpyAsync(loc_addr(x, m.to), loc_addr(x, m.from), nb * x->block_bytes, hipMemcpyDefault, x->move_stream);
+            if (e != hipSuccess) {
+                (void)hipGetLastError();
+                release_place(x, m.to, m.l);
+                moves_stop(x, IVF_ERR_HIP, std::string("copy of a list failed: ") + hipGetErrorString(e));
+                break;
+            }
+            b.moves.push_back(m);
+            b.bytes += nb * x->block_bytes;
+        }
+        if (b.moves.empty()) { x->spare_events.push_back(b.landed); break; }
+        hipError_t e = hipEventRecord(b.landed, x->move_stream);
+        if (e != hipSuccess) {
+            // the copies cannot be tracked: wait for them here, the batch then counts as landed
+            (void)hipGetLastError();
+            (void)hipStreamSynchronize(x->move_stream);
+            (void)hipEventRecord(b.landed, x->move_stream);
+        }
+        x->inflight_bytes += b.bytes;
+        x->inflight.push_back(std::move(b));
+    }
+    return 0;
+}
+
+// Blocks until no change is in progress.  With `cancel`, what has not been issued is dropped.
+int moves_drain(ivf_index* x, bool cancel) {
+    if (cancel && x->phase != kPhaseIdle) moves_stop(x, 0, "");
+    while (moves_active(x)) {
+        int rc = moves_advance(x);
+        if (rc) return rc;
+        if (!x->inflight.empty()) HIP_TRY(hipEventSynchronize(x->inflight.front().landed));
+        else if (!x->limbo.empty()) HIP_TRY(hipEventSynchronize(x->limbo.front().after));
+    }
+    return 0;
+}
+
+// Works out which lists have to change tier for a budget of `bytes` and queues the change.
+// The device is idle and no change is in progress.
+int budget_plan(ivf_index* x, int64_t bytes) {
+    const int64_t nlist = x->nlist;
+    x->moved_h2d = x->moved_d2h = x->moved_d2d = 0;
+    x->move_rc = 0;
+    x->move_msg.clear();
+    x->search_end_recorded = false;
+    // which lists are to be resident: ranked by the policy, while they fit
+    std::vector<uint32_t> hits;
+    if (x->opt_policy == 1) {
+        hits.resize((size_t)nlist);
+        HIP_TRY(hipMemcpy(hits.data(), x->d_hits, sizeof(uint32_t) * (size_t)nlist, hipMemcpyDeviceToHost));
+    }
+    std::vector<int32_t> order((size_t)nlist);
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (!hits.empty() && hits[a] != hits[b]) return hits[a] > hits[b];
+        if (x->len[a] != x->len[b]) return x->len[a] > x->len[b];
+        return a < b;
+    });
+    std::vector<char> res((size_t)nlist, 0);
+    uint64_t used = 0;
+    for (int32_t l : order) {
+        uint64_t b = (uint64_t)x->nblk[l] * x->block_bytes;
+        if (used + b > (uint64_t)bytes) break;
+        used += b;
+        res[l] = 1;
+    }
+    // evictions go least valuable first, loads most valuable first; a list without data
+    // just changes its label
+    bool relabelled = false;
+    for (auto it = order.rbegin(); it != order.rend(); ++it) {
+        const int32_t l = *it;
+        if (x->loc[l].tier != 0 || res[l]) continue;
+        if (x->nblk[l] == 0) { x->loc[l].tier = 1; x->resident_lists -= 1; relabelled = true; continue; }
+        Move m;
+        m.l = l; m.from = x->loc[l]; m.to.tier = 1;
+        x->todo.push_back(m);
+    }
+    for (int32_t l : order) {
+        if (x->loc[l].tier != 1 || !res[l]) continue;
+        if (x->nblk[l] == 0) { x->loc[l].tier = 0; x->resident_lists += 1; relabelled = true; continue; }
+        x->to_load.push_back(l);
+    }
+    if (relabelled) {
+        int rc = upload_list_ptr_table(x);
+        if (rc) return rc;
+    }
+    if (x->todo.empty() && x->to_load.empty()) return 0;
+    x->compact_wanted = !x->todo.empty();
+    x->phase = kPhaseEvict;
+    return 0;
+}
+
+void count_pending(const ivf_index* x, int64_t& lists, int64_t& bytes) {
+    lists = bytes = 0;
+    auto add = [&](int32_t l) { lists += 1; bytes += (int64_t)((size_t)x->nblk[l] * x->block_bytes); };
+    for (const MoveBatch& b : x->inflight)
+        for (const Move& m : b.moves)
+            if (m.from.tier != m.to.tier) add(m.l);
+    for (const Move& m : x->todo)
+        if (m.from.tier != m.to.tier) add(m.l);
+    for (int32_t l : x->to_load) add(l);
+}
+
 }  // namespace
 
 extern "C" {
@@ -598,6 +969,9 @@ int ivf_index_create(ivf_index** out) {
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, x->device);
     for (int i = 0; e == hipSuccess && i < kMaxSide; ++i) e = hipStreamCreateWithFlags(&x->side[i], hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->move_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->patch_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_search_end, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_probes, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_done, hipEventDisableTiming);
     for (int i = 0; e == hipSuccess && i < kMaxStage; ++i) {
@@ -621,6 +995,10 @@ void ivf_index_destroy(ivf_index* x) {
     free_index_data(x);
     for (int i = 0; i < kMaxSide; ++i)
         if (x->side[i]) (void)hipStreamDestroy(x->side[i]);
+    if (x->move_stream) (void)hipStreamDestroy(x->move_stream);
+    if (x->patch_stream) (void)hipStreamDestroy(x->patch_stream);
+    if (x->ev_search_end) (void)hipEventDestroy(x->ev_search_end);
+    for (hipEvent_t e : x->spare_events) (void)hipEventDestroy(e);
     if (x->ev_probes) (void)hipEventDestroy(x->ev_probes);
     if (x->ev_done) (void)hipEventDestroy(x->ev_done);
     for (int i = 0; i < kMaxStage; ++i) {
@@ -691,6 +1069,14 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
     if ((rc = dalloc(x->d_hits, (size_t)nlist, tot))) return rc;
     HIP_TRY(hipMemset(x->d_hits, 0, sizeof(uint32_t) * (size_t)nlist));
     {
+        hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&x->h_list_ptr), sizeof(void*) * (size_t)nlist);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            x->h_list_ptr = nullptr;
+            return fail(IVF_ERR_OOM_HOST, "pinned mirror of the list table: %s", hipGetErrorString(e));
+        }
+    }
+    {
         // segment size: a sixteenth of the index, between 64 MiB and the "segment_mb" option
         size_t total_bytes = (size_t)x->total_blocks * x->block_bytes;
         size_t seg_bytes = std::min<size_t>((size_t)x->opt_segment_mb << 20, std::max<size_t>((size_t)64 << 20, total_bytes / 16));
@@ -720,7 +1106,6 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
     HIP_TRY(hipMemcpy(x->d_offsets, x->offsets.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_len, x->len.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_nblk, x->nblk.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
-    refresh_list_ptrs(x);
     if ((rc = upload_list_ptr_table(x))) return rc;
     x->resident_lists = nlist;
     x->next_list = 0;
@@ -841,145 +1226,50 @@ int ivf_set_device_budget(ivf_index* x, int64_t bytes) {
     int rc = check_ready(x);
     if (rc) return rc;
     if (bytes < 0) return fail(IVF_ERR_INVALID, "budget must be non-negative");
+    if ((rc = moves_drain(x, true))) return rc;       // an earlier asynchronous change ends where it is
     HIP_TRY(hipDeviceSynchronize());
-    const int64_t nlist = x->nlist;
-    x->moved_h2d = x->moved_d2h = x->moved_d2d = 0;
-
-    // 1. which lists are to be resident: ranked by the policy, while they fit
-    std::vector<uint32_t> hits;
-    if (x->opt_policy == 1) {
-        hits.resize((size_t)nlist);
-        HIP_TRY(hipMemcpy(hits.data(), x->d_hits, sizeof(uint32_t) * (size_t)nlist, hipMemcpyDeviceToHost));
-    }
-    std::vector<int32_t> order((size_t)nlist);
-    std::iota(order.begin(), order.end(), 0);
-    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-        if (!hits.empty() && hits[a] != hits[b]) return hits[a] > hits[b];
-        if (x->len[a] != x->len[b]) return x->len[a] > x->len[b];
-        return a < b;
-    });
-    std::vector<char> res((size_t)nlist, 0);
-    uint64_t used = 0;
-    int64_t nres = 0;
-    for (int32_t l : order) {
-        uint64_t b = (uint64_t)x->nblk[l] * x->block_bytes;
-        if (used + b > (uint64_t)bytes) break;
-        used += b;
-        res[l] = 1;
-        ++nres;
-    }
-    std::vector<int32_t> evict, load;
-    for (int64_t l = 0; l < nlist; ++l) {
-        const bool is_res = x->loc[l].tier == 0;
-        if (is_res && !res[l]) evict.push_back((int32_t)l);
-        if (!is_res && res[l]) load.push_back((int32_t)l);
-    }
-    if (evict.empty() && load.empty()) return 0;
-
-    // Lists move with asynchronous copies on the default stream; a phase's sources are
-    // released only after the phase has been synchronised.  Only lists that change tier
-    // cross PCIe.  On an allocation failure the lists moved so far keep their new place
-    // (every list is always in exactly one valid place) and the error is returned.
-    struct Move { int32_t l; Loc from, to; };
-    std::vector<Move> moves;
-    hipError_t e = hipSuccess;
-    int err = 0;
-    auto addr = [&](const Loc& c) -> char* {
-        Pool& p = c.tier == 0 ? x->dpool : x->hpool;
-        return p.segs[c.seg].base + c.off * p.block_bytes;
-    };
-    auto run_phase = [&]() {       // wait for the copies, commit the moves, release the sources
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        for (const Move& m : moves) {
-            if (e == hipSuccess) {
-                x->loc[m.l] = m.to;
-                pool_release(m.from.tier == 0 ? x->dpool : x->hpool, m.from.seg, m.from.off, (size_t)x->nblk[m.l]);
-            } else {
-                pool_release(m.to.tier == 0 ? x->dpool : x->hpool, m.to.seg, m.to.off, (size_t)x->nblk[m.l]);
-            }
-        }
-        moves.clear();
-    };
-    auto move_list = [&](int32_t l, int to_tier, int exclude, bool may_grow) -> bool {
-        const size_t nb = (size_t)x->nblk[l];
-        Loc from = x->loc[l], to;
-        to.tier = (int8_t)to_tier;
-        if (!nb) { x->loc[l].tier = (int8_t)to_tier; return true; }
-        if (!pool_alloc(to_tier == 0 ? x->dpool : x->hpool, nb, to.seg, to.off, may_grow, exclude)) return false;
-        if (e == hipSuccess) e = hipMemcpyAsync(addr(to), addr(from), nb * x->block_bytes, hipMemcpyDefault, 0);
-        const int64_t by = (int64_t)(nb * x->block_bytes);
-        if (from.tier == 0 && to_tier == 1) x->moved_d2h += by;
-        else if (from.tier == 1 && to_tier == 0) x->moved_h2d += by;
-        else x->moved_d2d += by;
-        moves.push_back({l, from, to});
-        return true;
-    };
-
-    // 2. evictions: HBM -> pinned host
-    for (int32_t l : evict)
-        if (!move_list(l, 1, -1, true)) { err = fail(IVF_ERR_OOM_HOST, "out of pinned host memory while evicting list %d", l); break; }
-    run_phase();
-
-    // 3. compaction of the HBM pool: empty the least-filled segments into the holes of the
-    //    others (device-to-device copies) and give their memory back
-    if (!err && e == hipSuccess && !evict.empty()) {
-        std::vector<std::vector<int32_t>> in_seg(x->dpool.segs.size());
-        for (int64_t l = 0; l < nlist; ++l)
-            if (x->loc[l].tier == 0 && x->loc[l].seg >= 0) in_seg[x->loc[l].seg].push_back((int32_t)l);
-        std::vector<int> segs;
-        for (size_t i = 0; i < x->dpool.segs.size(); ++i)
-            if (x->dpool.segs[i].base) segs.push_back((int)i);
-        std::sort(segs.begin(), segs.end(), [&](int a, int b) { return x->dpool.segs[a].used < x->dpool.segs[b].used; });
-        for (int sidx : segs) {
-            Seg& g = x->dpool.segs[sidx];
-            if (g.used == 0) continue;
-            size_t free_elsewhere = 0;
-            for (size_t i = 0; i < x->dpool.segs.size(); ++i)
-                if ((int)i != sidx && x->dpool.segs[i].base) free_elsewhere += x->dpool.segs[i].blocks - x->dpool.segs[i].used;
-            if (free_elsewhere < g.used) break;        // segments are visited least-filled first
-            bool ok = true;
-            const size_t first = moves.size();
-            for (int32_t l : in_seg[sidx])
-                if (!move_list(l, 0, sidx, false)) { ok = false; break; }
-            if (!ok) {                                   // holes too small: leave this segment alone
-                for (size_t i = first; i < moves.size(); ++i) {
-                    pool_release(x->dpool, moves[i].to.seg, moves[i].to.off, (size_t)x->nblk[moves[i].l]);
-                    x->moved_d2d -= (int64_t)((size_t)x->nblk[moves[i].l] * x->block_bytes);
-                }
-                // copies already queued for them only wrote into holes that stay free
-                moves.resize(first);
-                continue;
-            }
-            run_phase();
-            for (int32_t l : in_seg[sidx]) in_seg[x->loc[l].seg].push_back(l);
-            in_seg[sidx].clear();
-            if (e != hipSuccess) break;
-        }
-        pool_drop_empty(x->dpool);
-    }
-
-    // 4. loads: pinned host -> HBM
-    if (!err && e == hipSuccess) {
-        for (int32_t l : load)
-            if (!move_list(l, 0, -1, true)) { err = fail(IVF_ERR_OOM_DEVICE, "out of device memory while loading list %d", l); break; }
-        run_phase();
-        pool_drop_empty(x->hpool);
-    }
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        err = fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(e));
-    }
-    refresh_list_ptrs(x);
-    nres = 0;
-    for (int64_t l = 0; l < nlist; ++l) nres += x->loc[l].tier == 0;
-    x->resident_lists = nres;
-    if ((rc = upload_list_ptr_table(x))) return rc;
-    if (err) return err;
-    if (nres < nlist) {
+    if ((rc = budget_plan(x, bytes))) return rc;
+    if ((rc = moves_drain(x, false))) return rc;
+    if (x->move_rc) return fail(x->move_rc, "%s", x->move_msg.c_str());
+    if (x->resident_lists < x->nlist) {
         if (!x->opt_host_direct && (rc = ensure_staging(x))) return rc;
     } else {
+        HIP_TRY(hipDeviceSynchronize());
         free_staging(x);
     }
+    return 0;
+}
+
+int ivf_set_device_budget_async(ivf_index* x, int64_t bytes) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (bytes < 0) return fail(IVF_ERR_INVALID, "budget must be non-negative");
+    if ((rc = moves_drain(x, true))) return rc;       // copies of an earlier change that are under way finish first
+    HIP_TRY(hipDeviceSynchronize());                  // searches issued so far are not tracked: let them end
+    if ((rc = budget_plan(x, bytes))) return rc;
+    if ((rc = moves_advance(x))) return rc;
+    if (x->move_rc) return fail(x->move_rc, "%s", x->move_msg.c_str());
+    return 0;
+}
+
+int ivf_budget_progress(ivf_index* x, int64_t* pending_lists, int64_t* pending_bytes, int* busy) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (moves_active(x) && (rc = moves_advance(x))) return rc;
+    int64_t pl = 0, pb = 0;
+    count_pending(x, pl, pb);
+    if (pending_lists) *pending_lists = pl;
+    if (pending_bytes) *pending_bytes = pb;
+    if (busy) *busy = moves_active(x) ? 1 : 0;
+    if (x->move_rc) return fail(x->move_rc, "%s", x->move_msg.c_str());
+    return 0;
+}
+
+int ivf_budget_wait(ivf_index* x) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if ((rc = moves_drain(x, false))) return rc;
+    if (x->move_rc) return fail(x->move_rc, "%s", x->move_msg.c_str());
     return 0;
 }
 
@@ -1003,6 +1293,13 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
             return fail(IVF_ERR_INVALID, "the index lives on HIP device %d but the current device is %d", x->device, dev);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool moving = moves_active(x);
+    if (moving) {
+        // a budget change is under way: take over what has landed, issue more copies, and
+        // let this search start only behind the latest update of the address table
+        if ((rc = moves_advance(x))) return rc;
+        if (!x->limbo.empty()) HIP_TRY(hipStreamWaitEvent(st, x->limbo.back().after, 0));
+    }
     const bool offload = x->resident_lists < x->nlist && !x->opt_host_direct;
     if (offload && (rc = ensure_staging(x))) return rc;
     if ((rc = ensure_scratch(x, nq, nprobe, offload))) {
@@ -1092,6 +1389,11 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     if (offload) {
         HIP_TRY(hipEventRecord(x->ev_done, st));
         x->done_recorded = true;
+    }
+    if (moving || moves_active(x)) {
+        // old places of moved lists are released only behind the searches that may read them
+        HIP_TRY(hipEventRecord(x->ev_search_end, st));
+        x->search_end_recorded = true;
     }
     x->last_nq = (int)nq;
     x->last_nprobe = nprobe;
@@ -1270,6 +1572,7 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
         // 1: the scan kernel reads host-resident lists straight from pinned host memory
         // (no staging copies); 0: they are copied with hipMemcpyAsync on the side stream
         if (x->opt_host_direct != value) {
+            if (moves_active(x)) return fail(IVF_ERR_INVALID, "host_direct cannot change while a budget change is in progress");
             x->opt_host_direct = value;
             if (x->ready) {
                 HIP_TRY(hipDeviceSynchronize());
@@ -1283,6 +1586,9 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     else if (n == "segment_mb" && value >= 1 && value <= 65536) x->opt_segment_mb = value;  // next upload
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
+    // asynchronous budget changes: size of one batch of list copies, and how much may be under way at once
+    else if (n == "move_chunk_kb" && value >= 1 && value <= ((int64_t)1 << 24)) x->opt_move_chunk_kb = value;
+    else if (n == "move_inflight_kb" && value >= 1 && value <= ((int64_t)1 << 26)) x->opt_move_inflight_kb = value;
     else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);
     return 0;
 }

@@ -49,6 +49,7 @@ struct ivf_worker {
     std::vector<double> t_ms;
     std::vector<int> t_n;
     ivf_worker_stats st = {};
+    int64_t wanted_budget = -1;                         // asked for and not yet taken up
 };
 
 namespace {
@@ -70,12 +71,50 @@ void worker_loop(ivf_worker* w) {
     for (int b = 1; b <= w->max_batch; b <<= 1) cands.push_back(b);
     if (cands.back() != w->max_batch) cands.push_back(w->max_batch);
     std::vector<Request> batch;
+    bool moving = false, started = false, finish = false;
+    int64_t budget = -1;
     while (ok) {
         batch.clear();
         {
             std::unique_lock<std::mutex> lk(w->mu);
-            w->cv_req.wait(lk, [&] { return w->stopping || !w->requests.empty(); });
-            if (w->requests.empty()) break;                    // stopping and drained
+            auto wake = [&] { return w->stopping || !w->requests.empty() || w->wanted_budget >= 0; };
+            if (moving) w->cv_req.wait_for(lk, std::chrono::milliseconds(1), wake);   // an idle worker keeps the change going
+            else w->cv_req.wait(lk, wake);
+            if (w->wanted_budget >= 0) {
+                budget = w->wanted_budget;
+                w->wanted_budget = -1;
+            }
+            finish = w->stopping && w->requests.empty();
+        }
+        if (budget >= 0 || moving) {
+            // budget changes run beside the searches: start one between two batches, then
+            // let every pass through the loop (and every search) carry it on
+            int brc = 0;
+            if (budget >= 0) {
+                brc = ivf_set_device_budget_async(w->idx, budget);
+                budget = -1;
+                started = true;
+            }
+            int64_t pl = 0, pb = 0;
+            int busy = 0;
+            if (!brc && finish) brc = ivf_budget_wait(w->idx);      // nothing left to serve: see the change through
+            if (!brc) brc = ivf_budget_progress(w->idx, &pl, &pb, &busy);
+            ivf_info info;
+            const bool have_info = ivf_get_info(w->idx, &info) == 0;
+            moving = !brc && busy != 0;
+            std::lock_guard<std::mutex> g(w->mu);
+            if (started) { w->st.budget_changes += 1; started = false; }
+            w->st.budget_pending_lists = brc ? 0 : pl;
+            w->st.budget_busy = (moving || w->wanted_budget >= 0) ? 1 : 0;
+            w->st.budget_error = brc;
+            if (have_info) w->st.resident_lists = info.resident_lists;
+        }
+        {
+            std::unique_lock<std::mutex> lk(w->mu);
+            if (w->requests.empty()) {
+                if (w->stopping && !moving && w->wanted_budget < 0) break;   // stopping and drained
+                continue;
+            }
             const int64_t n = (int64_t)w->requests.size();
             // batch size for this backlog: the backlog-aware rule once two batch sizes have
             // been timed, the whole backlog (up to max_batch) before that
@@ -209,6 +248,17 @@ int ivf_worker_get_stats(ivf_worker* w, ivf_worker_stats* out) {
     *out = w->st;
     out->queued = (int64_t)w->requests.size();
     out->results_waiting = (int64_t)w->done.size();
+    return 0;
+}
+
+int ivf_worker_set_device_budget(ivf_worker* w, int64_t bytes) {
+    if (!w || bytes < 0) return IVF_ERR_INVALID;
+    std::lock_guard<std::mutex> g(w->mu);
+    if (w->stopping) return IVF_ERR_INVALID;
+    if (w->failed) return w->fail_code;
+    w->wanted_budget = bytes;
+    w->st.budget_busy = 1;
+    w->cv_req.notify_one();
     return 0;
 }
 

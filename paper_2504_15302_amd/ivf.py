@@ -23,6 +23,7 @@ STAGES = ("coarse", "probe", "regroup", "scan", "stream", "select", "total")
 EXPORTS = (
     "ivf_index_create", "ivf_index_destroy", "ivf_index_upload", "ivf_index_upload_begin",
     "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
+    "ivf_set_device_budget_async", "ivf_budget_progress", "ivf_budget_wait", "ivf_worker_set_device_budget",
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
     "ivf_set_option", "ivf_debug_copy", "ivf_debug_read",
@@ -57,7 +58,9 @@ class SearchStats(C.Structure):
 class WorkerStats(C.Structure):
     _fields_ = [("requests_submitted", C.c_int64), ("requests_done", C.c_int64), ("batches", C.c_int64),
                 ("largest_batch", C.c_int64), ("queued", C.c_int64), ("results_waiting", C.c_int64),
-                ("fit_a_ms", C.c_double), ("fit_c", C.c_double)]
+                ("fit_a_ms", C.c_double), ("fit_c", C.c_double),
+                ("budget_changes", C.c_int64), ("budget_pending_lists", C.c_int64), ("budget_busy", C.c_int64),
+                ("resident_lists", C.c_int64), ("budget_error", C.c_int64)]
 
 
 _lib = None
@@ -87,6 +90,10 @@ def load_library() -> C.CDLL:
     lib.ivf_index_upload_lists.argtypes = [vp, i64, i64, vp, vp]
     lib.ivf_index_upload_end.argtypes = [vp]
     lib.ivf_set_device_budget.argtypes = [vp, i64]
+    lib.ivf_set_device_budget_async.argtypes = [vp, i64]
+    lib.ivf_budget_progress.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
+    lib.ivf_budget_wait.argtypes = [vp]
+    lib.ivf_worker_set_device_budget.argtypes = [vp, i64]
     lib.ivf_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.ivf_last_error.restype = C.c_char_p
     lib.ivf_get_info.argtypes = [vp, C.POINTER(Info)]
@@ -194,6 +201,18 @@ class Index:
         _check(self._lib.ivf_set_device_budget(self._h, int(nbytes)))
 
     # ---- search
+    def set_device_budget_async(self, nbytes: int):
+        _check(self._lib.ivf_set_device_budget_async(self._h, int(nbytes)))
+
+    def budget_progress(self):
+        """(lists still to change tier, their bytes, busy) after one non-blocking step."""
+        pl, pb, busy = C.c_int64(0), C.c_int64(0), C.c_int(0)
+        _check(self._lib.ivf_budget_progress(self._h, C.byref(pl), C.byref(pb), C.byref(busy)))
+        return pl.value, pb.value, bool(busy.value)
+
+    def budget_wait(self):
+        _check(self._lib.ivf_budget_wait(self._h))
+
     def search(self, queries, nprobe: int, k: int, out_ids=None, out_scores=None, stream=None):
         """queries: float32 CUDA tensor [nq, d].  Returns (ids int64 [nq,k], scores
         float32 [nq,k]) CUDA tensors; valid once `stream` (default: torch's current
@@ -337,6 +356,10 @@ class Worker:
             return None
         _check_plain(rc)
         return ids, scores
+
+    def set_device_budget(self, nbytes: int):
+        """Asks the worker to change its index's device budget in the background."""
+        _check_plain(self._lib.ivf_worker_set_device_budget(self._h, int(nbytes)))
 
     def stats(self) -> WorkerStats:
         out = WorkerStats()

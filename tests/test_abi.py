@@ -30,7 +30,7 @@ def test_header_symbols_are_all_exported_and_bound():
 def test_info_and_stats_structs_match_header_layout():
     assert C.sizeof(ivf.Info) == 8 + 13 * 8
     assert C.sizeof(ivf.SearchStats) == 7 * 8
-    assert C.sizeof(ivf.WorkerStats) == 8 * 8
+    assert C.sizeof(ivf.WorkerStats) == 13 * 8
 
 
 def test_null_arguments_return_error_codes_without_a_gpu():
@@ -39,6 +39,10 @@ def test_null_arguments_return_error_codes_without_a_gpu():
     assert b"NULL" in lib.ivf_last_error()
     assert lib.ivf_search(None, None, 1, 1, 1, None, None, None) == -1
     assert lib.ivf_set_device_budget(None, 0) == -1
+    assert lib.ivf_set_device_budget_async(None, 0) == -1
+    assert lib.ivf_budget_progress(None, None, None, None) == -1
+    assert lib.ivf_budget_wait(None) == -1
+    assert lib.ivf_worker_set_device_budget(None, 0) == -1
     assert lib.ivf_index_upload_end(None) == -1
     assert lib.ivf_set_option(None, b"scan_mode", 0) == -1
     assert lib.ivf_worker_start(None, 1, 1, 1, None) == -1
