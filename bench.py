@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time ivf_search at batch sizes 8..nq, fit T(B) = a*B^c and report the "
                          "backlog-aware batch-size choice (ivf_sched_*)")
+    ap.add_argument("--k-sweep", action="store_true",
+                    help="also time the search for k = 1..10 (the paper's range of retrieved chunks)")
     ap.add_argument("--budget-change", action="store_true",
                     help="also time a change of the device budget (to a quarter of the lists and back), "
                          "blocking and in the background while searches go on")
@@ -334,6 +336,20 @@ def main():
             "batch_sizes": sizes, "ms_per_search": times, "fit_a_ms": a, "fit_c": c,
             "queue": w.nq, "chosen_batch": best, "avg_latency_ms_from_queue_start": lat,
             "single_batch_beats_two": ivf_mod.sched_single_batch_is_best(c, 2)}
+    if args.k_sweep:
+        sweep = {}
+        for k in range(1, 11):
+            oi = torch.empty((w.nq, k), dtype=torch.int64, device="cuda")
+            os_ = torch.empty((w.nq, k), dtype=torch.float32, device="cuda")
+            for i in range(2):
+                idx.search(q_dev[i % nb], w.nprobe, k, oi, os_)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(8):
+                idx.search(q_dev[i % nb], w.nprobe, k, oi, os_)
+            torch.cuda.synchronize()
+            sweep[str(k)] = w.nq / ((time.perf_counter() - t0) / 8)
+        result["k_sweep_queries_per_s"] = sweep
     if args.budget_change:
         result["budget_change"] = budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log)
     if args.cpu_seconds > 0:

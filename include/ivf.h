@@ -255,7 +255,7 @@ int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
 
 /* ---- batch-size choice for the retrieval worker (host arithmetic, no GPU) ----
  *
- * Backlog-aware batch scheduling (paper Section 4.4, Eq. 4-8).  T(B) = a * B^c models
+ * Backlog-aware batch scheduling (paper Section 4.3, Eq. 4-8).  T(B) = a * B^c models
  * the time of one ivf_search over a batch of B queries; with n requests queued, k equal
  * batches served in turn give an average latency of (k+1)/2 * T(n/k) - mean arrival time
  * (Eq. 5 for k = 1, Eq. 6); one batch is at least as good as k batches iff
@@ -289,7 +289,7 @@ int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, i
  * a retrieval queue; a worker thread forms batches on its own, runs ivf_search on a
  * stream of its own and puts each request's result in a context queue, from which the
  * consumer (the generation side) takes it.  With a backlog of n requests the worker
- * serves them in batches of the size the backlog-aware rule picks (Section 4.4;
+ * serves them in batches of the size the backlog-aware rule picks (Section 4.3;
  * candidates 1, 2, 4, ... max_batch; T(B) fitted to the worker's own batch timings; the
  * whole backlog up to max_batch until two batch sizes have been timed).
  *

@@ -2,7 +2,7 @@
 TEST INFRASTRUCTURE ONLY (tests and the benchmark's reporting); shares no code with the
 library's implementation.
 
-Follows Section 4.4, "Backlog-aware Batch Scheduling (Online)", in the paper's order and
+Follows Section 4.3, "Backlog-aware Batch Scheduling (Online)", in the paper's order and
 notation, in plain fp64 Python:
 
   T(B)  = a * B**c, a > 0, c >= 0                      processing time of a batch of B   (Eq. 4)

@@ -15,7 +15,10 @@
  *   coarse      c(q,j) = sum_t Q[q,t]*C[j,t]                       fp64, t ascending
  *   probes      the nprobe lists with largest c(q,.), ties -> smaller list number
  *   scan        s(q,i) = sum_t Q[q,t]*X[i,t] for every i in a probed list, fp64,
- *               t ascending; fp16 storage is widened exactly before multiplying
+ *               t ascending; fp16 storage is widened exactly before multiplying;
+ *               int8 storage (a record of d signed codes and one fp32 scale per
+ *               vector, standing for the vector scale*codes) gives
+ *               s(q,i) = scale_i * sum_t Q[q,t]*code[i,t]
  *   select      candidates ordered by (s descending, user id ascending, position
  *               ascending); the first kout are reported, the rest padded (-1, -inf)
  *   assign      list of a vector = arg-max_j <x, C_j>, ties -> smaller j
@@ -61,6 +64,24 @@ static inline double elem(const void *x, int dtype, int64_t idx)
     if (dtype == 0)
         return (double)((const float *)x)[idx];
     return oracle_half_to_double(((const uint16_t *)x)[idx]);
+}
+
+/* <q, stored vector i> in fp64, t ascending.  dtype 2: rows are records of d int8 codes
+   followed by the vector's fp32 scale (d+4 bytes); the stored vector is scale*codes. */
+static double stored_dot(const void *X, int dtype, int64_t i, int d, const float *q)
+{
+    double s = 0.0;
+    if (dtype == 2) {
+        const unsigned char *row = (const unsigned char *)X + (size_t)i * ((size_t)d + 4);
+        float scale;
+        for (int t = 0; t < d; ++t)
+            s += (double)q[t] * (double)(signed char)row[t];
+        memcpy(&scale, row + d, sizeof scale);
+        return (double)scale * s;
+    }
+    for (int t = 0; t < d; ++t)
+        s += (double)q[t] * elem(X, dtype, i * d + t);
+    return s;
 }
 
 /* coarse[q*nlist + j] = <Q_q, C_j> in fp64 */
@@ -123,7 +144,8 @@ int oracle_probe_select(const double *coarse, int64_t nq, int64_t nlist, int npr
 }
 
 /* Exact scan of the given probe lists and sorted selection of the kout best.
- *   X        [n, d] list-major rows, dtype 0 = float32, 1 = IEEE binary16
+ *   X        [n, d] list-major rows, dtype 0 = float32, 1 = IEEE binary16,
+ *            2 = [n] records of d int8 codes + fp32 scale
  *   ids      [n] user ids; offsets [nlist+1]
  *   probes   [nq, nprobe] list numbers (a negative entry is skipped)
  *   out_ids  [nq, kout], out_scores [nq, kout] fp64 (pad: -1, -inf)
@@ -133,7 +155,7 @@ int oracle_scan_select(const void *X, int dtype, const int64_t *ids, const int64
                        int nprobe, int kout, int64_t *out_ids, double *out_scores)
 {
     if (!X || !ids || !offsets || !Q || !probes || !out_ids || !out_scores || d <= 0 ||
-        nprobe <= 0 || kout <= 0 || (dtype != 0 && dtype != 1))
+        nprobe <= 0 || kout <= 0 || dtype < 0 || dtype > 2)
         return -1;
     int err = 0;
 #pragma omp parallel for schedule(dynamic)
@@ -152,10 +174,7 @@ int oracle_scan_select(const void *X, int dtype, const int64_t *ids, const int64
             int32_t l = probes[q * nprobe + r];
             if (l < 0 || l >= nlist) continue;
             for (int64_t i = offsets[l]; i < offsets[l + 1]; ++i) {
-                double s = 0.0;
-                for (int t = 0; t < d; ++t)
-                    s += (double)Q[q * d + t] * elem(X, dtype, i * d + t);
-                c[m].s = s;
+                c[m].s = stored_dot(X, dtype, i, d, Q + q * d);
                 c[m].id = ids[i];
                 c[m].pos = i;
                 ++m;
@@ -180,7 +199,7 @@ int oracle_scan_select(const void *X, int dtype, const int64_t *ids, const int64
 int oracle_assign(const void *X, int dtype, int64_t n, const float *C, int64_t nlist, int d,
                   int32_t *list, double *best)
 {
-    if (!X || !C || !list || nlist <= 0 || d <= 0)
+    if (!X || !C || !list || nlist <= 0 || d <= 0 || (dtype != 0 && dtype != 1))
         return -1;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) {

@@ -59,7 +59,13 @@ def _vec(x: np.ndarray) -> Tuple[np.ndarray, int]:
         return np.ascontiguousarray(x), 0
     if x.dtype == np.float16:
         return np.ascontiguousarray(x), 1
-    raise TypeError("vectors must be float32 or float16")
+    if x.dtype == np.uint8:          # int8 storage: records of d codes + fp32 scale
+        return np.ascontiguousarray(x), 2
+    raise TypeError("vectors must be float32, float16 or uint8 records (int8 codes + fp32 scale)")
+
+
+def _dim(X: np.ndarray, dt: int) -> int:
+    return X.shape[1] - 4 if dt == 2 else X.shape[1]
 
 
 def threads() -> int:
@@ -99,7 +105,7 @@ def scan_select(vectors: np.ndarray, ids: np.ndarray, offsets: np.ndarray, Q: np
     Q = np.ascontiguousarray(Q, dtype=np.float32)
     probes = np.ascontiguousarray(probes, dtype=np.int32)
     nq, d = Q.shape
-    assert X.shape[1] == d and probes.shape[0] == nq
+    assert _dim(X, dt) == d and probes.shape[0] == nq
     nlist = offsets.shape[0] - 1
     out_ids = np.empty((nq, kout), dtype=np.int64)
     out_s = np.empty((nq, kout), dtype=np.float64)

@@ -1,7 +1,7 @@
 // Backlog-aware batch-size choice for the retrieval worker (host arithmetic only).
 // With n requests queued, serving them as k equal batches one after the other gives an
 // average latency of (k+1)/2 * T(n/k) minus the mean arrival time, where T(B) = a * B^c
-// is the profiled time of one batch (paper Section 4.4, Eq. 4-6); one batch beats k
+// is the profiled time of one batch (paper Section 4.3, Eq. 4-6); one batch beats k
 // batches exactly when 2 k^c <= k+1 (Eq. 7).  T is fitted to measured (B, T) samples of
 // ivf_search.  Exports the ivf_sched_* part of include/ivf.h.
 #include <cmath>

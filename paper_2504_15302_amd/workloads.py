@@ -50,7 +50,7 @@ class Workload:
     d: int
     nlist: int
     sigma: float
-    storage: str          # "fp32" | "fp16"
+    storage: str          # "fp32" | "fp16" | "int8" (records of d codes + fp32 scale)
     nq: int
     nprobe: int
     k: int
@@ -59,7 +59,12 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return 4 if self.storage == "fp32" else 2
+        return {"fp32": 4, "fp16": 2, "int8": 1}[self.storage]
+
+    @property
+    def row_bytes(self) -> int:
+        """Bytes of one stored vector as uploaded."""
+        return self.d * self.elem_bytes + (4 if self.storage == "int8" else 0)
 
     @property
     def ngroups(self) -> int:
@@ -75,6 +80,10 @@ CONFIGS = {
                    resident_list_frac=0.25),
     "C5": Workload("C5", 100_000_000, 768, 65536, 0.04, "fp16", 128, 128, 100, _MASTER + 4),
 }
+# The same indexes with compressed lists: every vector of the recipe, quantised to int8
+# codes with one scale per vector (quantize_int8_*).  Same seeds, same queries.
+for _name in ("C1", "C3", "C5"):
+    CONFIGS[_name + "-int8"] = replace(CONFIGS[_name], name=_name + "-int8", storage="int8")
 
 
 def scaled(w: Workload, **kw) -> Workload:
@@ -122,6 +131,42 @@ def queries(w: Workload, batch: int = 0, nq: Optional[int] = None) -> np.ndarray
     return out
 
 
+def quantize_int8_host(x: np.ndarray) -> np.ndarray:
+    """Data preparation for int8 storage: [rows, d] float32 -> [rows, d+4] uint8 records
+    of d signed codes followed by the vector's float32 scale (little endian).
+    scale = max|x| / 127 (1 for a zero vector), code = round-half-even(x / scale), all in
+    float32; the stored vector is scale * codes."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    rows, d = x.shape
+    scale = (np.abs(x).max(axis=1) / np.float32(127.0)).astype(np.float32) if d else np.zeros(rows, np.float32)
+    scale[scale == 0] = np.float32(1.0)
+    codes = np.clip(np.rint(x / scale[:, None]), -127, 127).astype(np.int8)
+    out = np.empty((rows, d + 4), dtype=np.uint8)
+    out[:, :d] = codes.view(np.uint8)
+    out[:, d:] = scale.view(np.uint8).reshape(rows, 4)
+    return out
+
+
+def quantize_int8_device(x):
+    """The same on a torch device tensor: [rows, d] float32 -> [rows, d+4] uint8."""
+    import torch
+    rows, d = x.shape
+    scale = x.abs().amax(dim=1) / 127.0
+    scale = torch.where(scale == 0, torch.ones_like(scale), scale)
+    codes = torch.clamp(torch.round(x / scale[:, None]), -127, 127).to(torch.int8)
+    out = torch.empty((rows, d + 4), dtype=torch.uint8, device=x.device)
+    out[:, :d] = codes.view(torch.uint8)
+    out[:, d:] = scale.contiguous().view(torch.uint8).reshape(rows, 4)
+    return out
+
+
+def split_int8_records(rec: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """[rows, d+4] uint8 records -> (codes [rows, d] int8, scales [rows] float32)."""
+    rec = np.ascontiguousarray(rec, dtype=np.uint8)
+    d = rec.shape[1] - 4
+    return rec[:, :d].view(np.int8), np.ascontiguousarray(rec[:, d:]).view(np.float32).reshape(-1)
+
+
 def _group_rows(w: Workload, off: np.ndarray, group: int) -> Tuple[int, int, int, int]:
     l0 = group * GROUP
     l1 = min(w.nlist, l0 + GROUP)
@@ -130,13 +175,15 @@ def _group_rows(w: Workload, off: np.ndarray, group: int) -> Tuple[int, int, int
 
 def group_vectors_host(w: Workload, cen: np.ndarray, off: np.ndarray, group: int) -> np.ndarray:
     """Row-major vectors of the lists of one group, list after list, in the
-    storage type (float32 or float16), drawn with NumPy."""
+    storage type (float32, float16, or int8 records), drawn with NumPy."""
     l0, l1, r0, r1 = _group_rows(w, off, group)
     rows = r1 - r0
     g = _rng(w, _STREAM_NOISE, group).standard_normal((rows, w.d), dtype=np.float32)
     label = np.repeat(np.arange(l0, l1), np.diff(off[l0:l1 + 1]))
     x = cen[label] + np.float32(w.sigma) * g
     x /= np.linalg.norm(x, axis=1, keepdims=True)
+    if w.storage == "int8":
+        return quantize_int8_host(x)
     return x.astype(np.float16 if w.storage == "fp16" else np.float32)
 
 
@@ -156,7 +203,8 @@ def group_vectors_device(w: Workload, cen_dev, off: np.ndarray, group_begin: int
         label = torch.repeat_interleave(torch.arange(l0, l1, device=device), sizes)
         g.mul_(w.sigma).add_(cen_dev[label])
         g.div_(torch.linalg.vector_norm(g, dim=1, keepdim=True))
-        parts.append(g.to(torch.float16) if w.storage == "fp16" else g)
+        parts.append(quantize_int8_device(g) if w.storage == "int8" else
+                     g.to(torch.float16) if w.storage == "fp16" else g)
     return torch.cat(parts, dim=0) if len(parts) != 1 else parts[0]
 
 

@@ -1,4 +1,4 @@
-"""Backlog-aware batch-size choice (paper Section 4.4, Eq. 4-8): pins for the oracle and
+"""Backlog-aware batch-size choice (paper Section 4.3, Eq. 4-8): pins for the oracle and
 parity of the library's ivf_sched_* functions against it (host arithmetic, no GPU)."""
 import math
 import os

@@ -69,6 +69,22 @@ def test_c1_other_k_nprobe_nq(c1, k, nprobe, nq):
     check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, nprobe, k, got, w.storage)
 
 
+def test_k_sweep_1_to_10(c1):
+    """The paper's sensitivity study varies the number of retrieved chunks from 1 to 10
+    (Section 6.5, "Number of Retrieval Chunks"): every k against the oracle, and each
+    result the prefix of the next."""
+    w, h, idx = c1
+    q = W.queries(w, batch=5)
+    prev = None
+    for k in range(1, 11):
+        say(f"C1: k={k}")
+        got = gpu_search(idx, q, w.nprobe, k)
+        check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, k, got, w.storage)
+        if prev is not None:
+            assert np.array_equal(got[0][:, :k - 1], prev[0]) and np.array_equal(got[1][:, :k - 1], prev[1])
+        prev = got
+
+
 def test_rows_do_not_depend_on_the_batch(c1):
     w, h, idx = c1
     q = W.queries(w, batch=1)
