@@ -22,9 +22,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per k_scan launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE, both
-# scaled against the library's plain copy kernel): profiles/k_scan_C5_pmc_traffic.md.
-# Only the default workload has been counted; the others report null.
-TRAFFIC_BYTES = {"C5": 1.66726e7 * 2.000 * 1024 + 5510.66 * 1024}
+# scaled against the library's plain copy kernel), and the summary each comes from.
+# Workloads that have not been counted report null.
+TRAFFIC_BYTES = {"C5": 1.66726e7 * 2.000 * 1024 + 5510.66 * 1024,
+                 "C5-int8": 8.38707e6 * 2.000 * 1024 + 5454.83 * 1024}
+TRAFFIC_SOURCE = {"C5": "profiles/k_scan_C5_pmc_traffic.md",
+                  "C5-int8": "profiles/k_scan_C5_int8_trace_and_traffic.md"}
 
 
 def log(msg):
@@ -40,7 +43,7 @@ def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
     from paper_2504_15302_amd import ivf
 
     w = lw.w
-    dt = ivf.IVF_FP16 if w.storage == "fp16" else ivf.IVF_FP32
+    dt = {"fp32": ivf.IVF_FP32, "fp16": ivf.IVF_FP16, "int8": ivf.IVF_INT8}[w.storage]
 
     def run(rows):
         qs = q[rows]
@@ -90,7 +93,7 @@ def budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log):
     lens = np.diff(lw.offsets)
     order = np.lexsort((np.arange(w.nlist), -lens))
     keep = order[: w.nlist // 4]
-    quarter = int(((lens[keep] + 63) // 64).sum()) * 64 * w.d * w.elem_bytes
+    quarter = int(((lens[keep] + 63) // 64).sum()) * 64 * w.row_bytes
     start = idx.info().device_list_bytes
     nb = len(q_dev)
 
@@ -184,7 +187,7 @@ def main():
         lens = np.diff(lw.offsets)
         order = np.lexsort((np.arange(w.nlist), -lens))
         keep = order[: int(w.nlist * w.resident_list_frac)]
-        budget = int(((lens[keep] + 63) // 64).sum()) * 64 * w.d * w.elem_bytes
+        budget = int(((lens[keep] + 63) // 64).sum()) * 64 * w.row_bytes
         idx.set_device_budget(budget)
         log(f"device budget {budget / 2**30:.2f} GiB: {idx.info().resident_lists} lists resident")
 
@@ -271,7 +274,7 @@ def main():
         "metric": "queries/sec and list-scan HBM GB/s (% of peak), batched IVF top-k search",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 accumulate over " + ("f16" if w.storage == "fp16" else "f32") + " storage",
+        "dtype": "f32 accumulate over " + {"fp32": "f32", "fp16": "f16", "int8": "i8 codes + f32 scale"}[w.storage] + " storage",
         "data": "synthetic (seeded Gaussian mixture, generated on the GPU; random-init, no dataset)",
         "config": {"workload": f"{w.name}: IVF-Flat inner product, N={w.n}, d={w.d}, {w.storage} storage, "
                                f"nlist={w.nlist}, nq={w.nq}, nprobe={w.nprobe}, k={w.k}"
@@ -284,7 +287,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": TRAFFIC_BYTES.get(w.name) if not args.option else None,
-                     "traffic_source": "profiles/k_scan_C5_pmc_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+                     "traffic_source": TRAFFIC_SOURCE[w.name] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
                                        "bytes per launch)" if (w.name in TRAFFIC_BYTES and not args.option) else None,
                      "bytes_per_launch": avg_scan_bytes, "ms_per_launch": avg_scan_ms,
                      "launches_timed": kept,

@@ -46,7 +46,18 @@ typedef enum {
     IVF_ERR_LIMIT = -5      /* argument beyond a documented limit */
 } ivf_status;
 
-enum { IVF_FP32 = 0, IVF_FP16 = 1 };
+/*
+ * Storage types of the list data.  IVF_INT8 is the compressed form (the paper points at
+ * quantised / on-disk indexes as the way to trade memory for accuracy, Section 6.5
+ * "On-Disk Index", without fixing a format; this one is the build's own): each stored
+ * vector is a record of d signed 8-bit codes followed by one fp32 scale (d+4 bytes, little
+ * endian, d a multiple of 16) and stands for the vector scale*codes, so that
+ *     score(q, i) = scale_i * sum_t q_t * code_{i,t}        (fp32 accumulate)
+ * exactly as for the other types but over 1 byte per dimension.  Quantising the
+ * embeddings (choice of scale, rounding) is data preparation by the caller, like the
+ * assignment to lists: the search is exact over the vectors the records stand for.
+ */
+enum { IVF_FP32 = 0, IVF_FP16 = 1, IVF_INT8 = 2 };
 
 /* Creates an empty index bound to the current HIP device. */
 int ivf_index_create(ivf_index **out);
@@ -61,8 +72,8 @@ void ivf_index_destroy(ivf_index *idx);
  *   nlist         number of inverted lists (= number of centroids)
  *   n             number of stored vectors
  *   centroids     [nlist, d] fp32 row-major, host or device
- *   vectors       [n, d] row-major in list order, fp32 or IEEE binary16 per `dtype`,
- *                 host or device
+ *   vectors       [n, d] row-major in list order, fp32 or IEEE binary16 per `dtype`
+ *                 (IVF_INT8: [n] records of d+4 bytes, see above), host or device
  *   ids           [n] user ids in the same order, host or device
  *   list_offsets  [nlist+1], list j owns rows [list_offsets[j], list_offsets[j+1]);
  *                 list_offsets[0] = 0, list_offsets[nlist] = n; host or device

@@ -12,7 +12,7 @@ from typing import List, Optional
 import numpy as np
 
 TIE_REL = 1e-5
-SCORE_REL = {"fp32": 1e-5, "fp16": 2e-3}
+SCORE_REL = {"fp32": 1e-5, "fp16": 2e-3, "int8": 1e-5}   # int8: exact codes, fp32 accumulate
 
 
 def _near(a: float, b: float, rel: float, floor: float = 0.0) -> bool:

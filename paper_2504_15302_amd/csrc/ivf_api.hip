@@ -158,7 +158,8 @@ struct ivf_index {
     bool uploading = false, ready = false;
     int d = 0, dtype = 0, es = 4;
     int64_t nlist = 0, n = 0, next_list = 0;
-    size_t row_bytes = 0, block_bytes = 0;
+    size_t row_bytes = 0, block_bytes = 0;      // one stored vector as uploaded; 64 of them, blocked
+    int tail_bytes = 0;                         // bytes of a row behind its d elements (int8: the scale)
     int64_t total_blocks = 0, max_len = 0;
     std::vector<int64_t> offsets, blk_off;
     std::vector<int32_t> len, nblk;
@@ -506,25 +507,25 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
     return 0;
 }
 
-template <bool HALF, int U, int WAVES>
+template <int ST, int U, int WAVES>
 void launch_scan_k(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
                    const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
     Scratch& s = x->sc;
     unsigned int* queue = reinterpret_cast<unsigned int*>(s.zeroed + 2 * (size_t)x->nlist);
     dim3 grid = mode == 0 ? dim3((unsigned)((work_items + WAVES - 1) / WAVES))
                           : dim3((unsigned)(x->cus * std::max<int64_t>(1, x->opt_scan_wgs_per_cu)));
-    hipLaunchKernelGGL((k_scan<HALF, U, WAVES>), grid, dim3(WAVES * 64), 0, st, items, n_dev, n_host, Q, x->d,
+    hipLaunchKernelGGL((k_scan<ST, U, WAVES>), grid, dim3(WAVES * 64), 0, st, items, n_dev, n_host, Q, x->d,
                        s.scores, s.bmax, mode, queue, s.qthr, x->prune_blocks, x->prune_j);
 }
 
-template <bool HALF, int U>
+template <int ST, int U>
 void launch_scan_w(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
                    const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
     switch ((int)x->opt_scan_waves) {
-        case 1: launch_scan_k<HALF, U, 1>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        case 2: launch_scan_k<HALF, U, 2>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        case 8: launch_scan_k<HALF, U, 8>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        default: launch_scan_k<HALF, U, 4>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        case 1: launch_scan_k<ST, U, 1>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        case 2: launch_scan_k<ST, U, 2>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        case 8: launch_scan_k<ST, U, 8>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
+        default: launch_scan_k<ST, U, 4>(x, work_items, st, items, n_dev, n_host, Q, mode);
     }
 }
 
@@ -533,11 +534,14 @@ void launch_scan(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem
                  const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
     const int U = (int)x->opt_scan_unroll;
     if (x->dtype == IVF_FP16) {
-        if (U == 8) launch_scan_w<true, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
-        else launch_scan_w<true, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        if (U == 8) launch_scan_w<kF16, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        else launch_scan_w<kF16, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+    } else if (x->dtype == IVF_INT8) {
+        if (U == 8) launch_scan_w<kI8, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        else launch_scan_w<kI8, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
     } else {
-        if (U == 8) launch_scan_w<false, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
-        else launch_scan_w<false, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        if (U == 8) launch_scan_w<kF32, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        else launch_scan_w<kF32, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
     }
 }
 
@@ -1015,16 +1019,19 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
                            int dtype, const int64_t* list_offsets) {
     if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
     if (!centroids || !list_offsets) return fail(IVF_ERR_INVALID, "centroids or list_offsets is NULL");
-    if (dtype != IVF_FP32 && dtype != IVF_FP16) return fail(IVF_ERR_INVALID, "dtype must be IVF_FP32 or IVF_FP16");
+    if (dtype != IVF_FP32 && dtype != IVF_FP16 && dtype != IVF_INT8)
+        return fail(IVF_ERR_INVALID, "dtype must be IVF_FP32, IVF_FP16 or IVF_INT8");
     if (d <= 0 || nlist <= 0 || n < 0) return fail(IVF_ERR_INVALID, "d, nlist must be positive and n non-negative");
     if (d % 8 != 0 || d > 4096) return fail(IVF_ERR_LIMIT, "d must be a multiple of 8 and at most 4096 (got %d)", d);
+    if (dtype == IVF_INT8 && d % 16 != 0) return fail(IVF_ERR_LIMIT, "d must be a multiple of 16 for int8 storage (got %d)", d);
     if (n >= (int64_t)1 << 32 || nlist >= (int64_t)1 << 31)
         return fail(IVF_ERR_LIMIT, "n must be below 2^32 and nlist below 2^31");
     (void)hipDeviceSynchronize();
     free_index_data(x);
-    x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : 4;
+    x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : dtype == IVF_INT8 ? 1 : 4;
     x->nlist = nlist; x->n = n;
-    x->row_bytes = (size_t)d * x->es;
+    x->tail_bytes = dtype == IVF_INT8 ? 4 : 0;       // int8 records end with their fp32 scale
+    x->row_bytes = (size_t)d * x->es + x->tail_bytes;
     x->block_bytes = x->row_bytes * kLanes;
     try {
         x->offsets.assign((size_t)nlist + 1, 0);
@@ -1158,7 +1165,7 @@ int ivf_index_upload_lists(ivf_index* x, int64_t list_begin, int64_t list_end, c
                 if (e == hipSuccess) {
                     dim3 grid((unsigned)(le - lb), (unsigned)maxnb);
                     hipLaunchKernelGGL(k_relayout, grid, dim3(256), 0, 0, src, x->d_offsets, x->d_list_ptr, lb,
-                                       (int)x->row_bytes);
+                                       (int)x->row_bytes, x->tail_bytes);
                     e = hipGetLastError();
                     if (e == hipSuccess) e = hipDeviceSynchronize();
                 }
@@ -1463,7 +1470,8 @@ int ivf_debug_read_list(ivf_index* x, int64_t list, void* out_vectors, int64_t* 
             src = blk;
         }
         if (e == hipSuccess) {
-            hipLaunchKernelGGL(k_unlayout, dim3((unsigned)x->nblk[list]), dim3(256), 0, 0, src, ln, (int)x->row_bytes, rows);
+            hipLaunchKernelGGL(k_unlayout, dim3((unsigned)x->nblk[list]), dim3(256), 0, 0, src, ln, (int)x->row_bytes,
+                               x->tail_bytes, rows);
             e = hipGetLastError();
         }
         if (e == hipSuccess) e = hipMemcpy(out_vectors, rows, (size_t)ln * x->row_bytes, hipMemcpyDeviceToHost);

@@ -2,9 +2,10 @@
 // that probes the list.  HBM-bound (about one multiply-add per byte loaded), so the
 // kernel is built around the loads:
 //   * storage is blocked as [block of 64 vectors][d/E chunks][64 lanes][16 bytes]
-//     (E = 8 for fp16, 4 for fp32): a lane owns one vector, every load instruction of
-//     a wavefront fetches one contiguous 1 KiB line, and no cross-lane reduction is
-//     needed for the dot product;
+//     (E = 8 for fp16, 4 for fp32, 16 for int8 codes): a lane owns one vector, every
+//     load instruction of a wavefront fetches one contiguous 1 KiB line, and no
+//     cross-lane reduction is needed for the dot product; int8 blocks end with the 64
+//     fp32 scales of their vectors (the stored vector is scale * codes);
 //   * a wavefront streams one block (64*d*elem bytes, contiguous) with two register
 //     buffers of U loads each, so loads of the next chunk group are in flight while
 //     the current one is multiplied;
@@ -39,9 +40,12 @@ __device__ __forceinline__ float wave_max(float v, int lane) {
     return v;
 }
 
-template <bool HALF> struct Store;
-template <> struct Store<true> { static constexpr int E = 8; };
-template <> struct Store<false> { static constexpr int E = 4; };
+// storage types (the dtype codes of the C ABI)
+constexpr int kF32 = 0, kF16 = 1, kI8 = 2;
+template <int ST> struct Store;
+template <> struct Store<kF32> { static constexpr int E = 4; };
+template <> struct Store<kF16> { static constexpr int E = 8; };
+template <> struct Store<kI8> { static constexpr int E = 16; };
 
 // One group of UU consecutive 16-byte chunks of the lane's vector plus the matching
 // slice of each query, spread one value per lane (lane j holds dimension dim0 + j).
@@ -72,50 +76,62 @@ __device__ __forceinline__ void load_group(ScanBuf<NQ, UU, E>& b, gptr_u4 src, i
 
 // acc[g] += sum over the group's dimensions of x * q[g]; the query value of a
 // dimension is broadcast from the lane that holds it and enters the FMA as a scalar.
-template <bool HALF, int NQ, int UU, int E>
+// Eight dimensions at a time (half a chunk of int8 codes), so that the broadcast values
+// of one step fit the scalar registers.
+template <int ST, int NQ, int UU, int E>
 __device__ __forceinline__ void fma_group(const ScanBuf<NQ, UU, E>& b, float (&acc)[NQ]) {
+    constexpr int S = E < 8 ? E : 8;             // dimensions per step
 #pragma unroll
     for (int u = 0; u < UU; ++u) {
-        float xf[E];
-        if constexpr (HALF) {
-            h8 x = __builtin_bit_cast(h8, b.x[u]);
 #pragma unroll
-            for (int h = 0; h < E; ++h) xf[h] = (float)x[h];
-        } else {
-            f4 x = __builtin_bit_cast(f4, b.x[u]);
+        for (int h0 = 0; h0 < E; h0 += S) {
+            float xf[S];
+            if constexpr (ST == kF16) {
+                h8 x = __builtin_bit_cast(h8, b.x[u]);
 #pragma unroll
-            for (int h = 0; h < E; ++h) xf[h] = x[h];
+                for (int h = 0; h < S; ++h) xf[h] = (float)x[h];
+            } else if constexpr (ST == kF32) {
+                f4 x = __builtin_bit_cast(f4, b.x[u]);
+#pragma unroll
+                for (int h = 0; h < S; ++h) xf[h] = x[h];
+            } else {
+#pragma unroll
+                for (int h = 0; h < S; ++h) {
+                    const unsigned w = b.x[u][(h0 + h) / 4];
+                    xf[h] = (float)(int)(signed char)(w >> (8 * ((h0 + h) % 4)));
+                }
+            }
+            // The empty asm makes the query register opaque here, so the lane reads of this
+            // step stay next to its FMAs; hoisted to the load they would need 64 scalar
+            // registers per query and spill.
+            float qreg[NQ];
+#pragma unroll
+            for (int g = 0; g < NQ; ++g) {
+                qreg[g] = b.q[g][(u * E + h0) / 64];
+                asm volatile("" : "+v"(qreg[g]));
+            }
+            float qs[NQ][S];
+#pragma unroll
+            for (int h = 0; h < S; ++h)
+#pragma unroll
+                for (int g = 0; g < NQ; ++g)
+                    qs[g][h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[g]), (u * E + h0 + h) % 64));
+#pragma unroll
+            for (int h = 0; h < S; ++h)
+#pragma unroll
+                for (int g = 0; g < NQ; ++g) acc[g] = __builtin_fmaf(xf[h], qs[g][h], acc[g]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // The empty asm makes the query register opaque here, so the lane reads of this
-        // chunk stay next to its FMAs; hoisted to the load they would need 64 scalar
-        // registers per query and spill.
-        float qreg[NQ];
-#pragma unroll
-        for (int g = 0; g < NQ; ++g) {
-            qreg[g] = b.q[g][(u * E) / 64];
-            asm volatile("" : "+v"(qreg[g]));
-        }
-        float qs[NQ][E];
-#pragma unroll
-        for (int h = 0; h < E; ++h)
-#pragma unroll
-            for (int g = 0; g < NQ; ++g)
-                qs[g][h] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(qreg[g]), (u * E + h) % 64));
-#pragma unroll
-        for (int h = 0; h < E; ++h)
-#pragma unroll
-            for (int g = 0; g < NQ; ++g) acc[g] = __builtin_fmaf(xf[h], qs[g][h], acc[g]);
-        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-template <bool HALF, int NQ, int U>
+template <int ST, int NQ, int U>
 __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __restrict__ Q,
                                           int d, float* __restrict__ scores,
                                           float* __restrict__ bmax, int lane,
                                           unsigned long long* __restrict__ qthr, int prune_blocks,
                                           int prune_j) {
-    constexpr int E = Store<HALF>::E;
+    constexpr int E = Store<ST>::E;
     const int nchunk = d / E;
     const int nq = (int)it.nq;
     // lanes past the end of the list re-read the last valid vector (same cache lines,
@@ -131,6 +147,9 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
     float acc[NQ];
 #pragma unroll
     for (int g = 0; g < NQ; ++g) acc[g] = 0.f;
+    float scale = 1.f;                              // int8: the lane's scale sits behind the codes
+    if constexpr (ST == kI8)
+        scale = *(reinterpret_cast<const float*>(static_cast<const char*>(it.data) + (size_t)nchunk * kLanes * 16) + ld_lane);
 
     // two register buffers: the loads of group i+1 are in flight while group i is used
     ScanBuf<NQ, U, E> bufA, bufB;
@@ -140,29 +159,29 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
         load_group(bufA, src, 0, qrow, lane);
         for (; gi + 2 < ngroup; gi += 2) {           // bufA holds group gi
             load_group(bufB, src, (gi + 1) * U, qrow, lane);
-            fma_group<HALF>(bufA, acc);
+            fma_group<ST>(bufA, acc);
             load_group(bufA, src, (gi + 2) * U, qrow, lane);
-            fma_group<HALF>(bufB, acc);
+            fma_group<ST>(bufB, acc);
         }
         if (gi + 1 < ngroup) {
             load_group(bufB, src, (gi + 1) * U, qrow, lane);
-            fma_group<HALF>(bufA, acc);
-            fma_group<HALF>(bufB, acc);
+            fma_group<ST>(bufA, acc);
+            fma_group<ST>(bufB, acc);
         } else {
-            fma_group<HALF>(bufA, acc);
+            fma_group<ST>(bufA, acc);
         }
     }
     for (int c = ngroup * U; c < nchunk; ++c) {     // d not a multiple of the group width
         ScanBuf<NQ, 1, E> one;
         load_group(one, src, c, qrow, lane);
-        fma_group<HALF>(one, acc);
+        fma_group<ST>(one, acc);
     }
 
     const bool valid = lane < (int)it.nvalid;
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
         if (g < nq) {
-            const float s = valid ? acc[g] : -INFINITY;
+            const float s = valid ? (ST == kI8 ? acc[g] * scale : acc[g]) : -INFINITY;
             const uint32_t sb = it.sblk + (uint32_t)g * it.nblk;
             const float mx = wave_max(s, lane);
             bool store = true;
@@ -207,18 +226,18 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
     }
 }
 
-template <bool HALF, int U>
+template <int ST, int U>
 __device__ __forceinline__ void scan_dispatch(const ScanItem& it, const float* __restrict__ Q,
                                               int d, float* __restrict__ scores,
                                               float* __restrict__ bmax, int lane,
                                               unsigned long long* __restrict__ qthr,
                                               int prune_blocks, int prune_j) {
     if (it.nq == 1)
-        scan_item<HALF, 1, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+        scan_item<ST, 1, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     else if (it.nq == 2)
-        scan_item<HALF, 2, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+        scan_item<ST, 2, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     else
-        scan_item<HALF, kQB, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+        scan_item<ST, kQB, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
 }
 
 constexpr int kScanWaves = 4;   // default wavefronts per workgroup of the scan
@@ -227,7 +246,7 @@ constexpr int kScanWaves = 4;   // default wavefronts per workgroup of the scan
 // mode 1: persistent wavefronts pulling items from an atomic queue (*queue must be 0).
 // The item count comes from device memory (n_items_dev) when the plan was made on the
 // device, else from the host (n_items_host).
-template <bool HALF, int U, int WAVES>
+template <int ST, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_scan(
     const ScanItem* __restrict__ items, const unsigned long long* __restrict__ n_items_dev,
     uint32_t n_items_host, const float* __restrict__ Q, int d, float* __restrict__ scores,
@@ -240,7 +259,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scan(
         uint32_t t = blockIdx.x * WAVES + wave;
         if (t >= T) return;
         ScanItem it = items[t];
-        scan_dispatch<HALF, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+        scan_dispatch<ST, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
     } else {
         for (;;) {
             // All 64 lanes take part in the atomic (lane 0 adds 1, the others 0) so that
@@ -251,43 +270,74 @@ __global__ __launch_bounds__(WAVES * 64) void k_scan(
             t = __builtin_amdgcn_readfirstlane(t);
             if (t >= T) break;           // every wavefront reaches this: the queue only grows
             ScanItem it = items[t];
-            scan_dispatch<HALF, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+            scan_dispatch<ST, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
         }
     }
 }
 
 // Upload-time re-layout: row-major rows of a piece of the index -> blocked storage.
-// grid.x = list within the piece, grid.y = block within the list.
+// A row is `row_bytes - tail_bytes` bytes of elements (a multiple of 16) followed by
+// `tail_bytes` (0, or 4: the scale of an int8 record); a block holds the element chunks
+// of its 64 vectors and then their 64 tails.  grid.x = list within the piece, grid.y =
+// block within the list.
 __global__ __launch_bounds__(256) void k_relayout(const char* __restrict__ src_rows,
                                                   const int64_t* __restrict__ offsets,
                                                   const void* const* __restrict__ list_ptr,
-                                                  int64_t list_begin, int row_bytes) {
+                                                  int64_t list_begin, int row_bytes, int tail_bytes) {
     const int64_t l = list_begin + blockIdx.x;
     const int64_t len = offsets[l + 1] - offsets[l];
     const int64_t b = blockIdx.y;
     if (b * kLanes >= len) return;
     const int64_t row0 = offsets[l] - offsets[list_begin] + b * kLanes;
-    const int nchunk = row_bytes / 16;
-    u4* dst = reinterpret_cast<u4*>(static_cast<char*>(const_cast<void*>(list_ptr[l])) + (size_t)b * kLanes * (size_t)row_bytes);
-    for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
-        int c = u / kLanes, lane = u % kLanes;
-        u4 v = {0u, 0u, 0u, 0u};
-        if (b * kLanes + lane < len)
-            v = *reinterpret_cast<const u4*>(src_rows + (size_t)(row0 + lane) * row_bytes + (size_t)c * 16);
-        dst[u] = v;
+    const int nchunk = (row_bytes - tail_bytes) / 16;
+    char* blk = static_cast<char*>(const_cast<void*>(list_ptr[l])) + (size_t)b * kLanes * (size_t)row_bytes;
+    if (tail_bytes == 0) {                   // rows are 16-byte aligned
+        u4* dst = reinterpret_cast<u4*>(blk);
+        for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
+            int c = u / kLanes, lane = u % kLanes;
+            u4 v = {0u, 0u, 0u, 0u};
+            if (b * kLanes + lane < len)
+                v = *reinterpret_cast<const u4*>(src_rows + (size_t)(row0 + lane) * row_bytes + (size_t)c * 16);
+            dst[u] = v;
+        }
+    } else {                                 // rows are 4-byte aligned: word by word
+        unsigned* dst = reinterpret_cast<unsigned*>(blk);
+        for (int u = threadIdx.x; u < nchunk * kLanes * 4; u += 256) {
+            int c = u / (kLanes * 4), lane = (u / 4) % kLanes, wd = u % 4;
+            unsigned v = 0u;
+            if (b * kLanes + lane < len)
+                v = *reinterpret_cast<const unsigned*>(src_rows + (size_t)(row0 + lane) * row_bytes + (size_t)c * 16 + wd * 4);
+            dst[u] = v;
+        }
+        unsigned* tails = dst + (size_t)nchunk * kLanes * 4;
+        const int tw = tail_bytes / 4;
+        for (int u = threadIdx.x; u < kLanes * tw; u += 256) {
+            int lane = u / tw, wd = u % tw;
+            unsigned v = 0u;
+            if (b * kLanes + lane < len)
+                v = *reinterpret_cast<const unsigned*>(src_rows + (size_t)(row0 + lane) * row_bytes + (row_bytes - tail_bytes) + wd * 4);
+            tails[u] = v;
+        }
     }
 }
 
 // Inverse of k_relayout for one list (debug read-back).
 __global__ __launch_bounds__(256) void k_unlayout(const char* __restrict__ blocks, int64_t len,
-                                                  int row_bytes, char* __restrict__ dst_rows) {
+                                                  int row_bytes, int tail_bytes, char* __restrict__ dst_rows) {
     const int64_t b = blockIdx.x;
-    const int nchunk = row_bytes / 16;
-    const u4* src = reinterpret_cast<const u4*>(blocks + (size_t)b * kLanes * (size_t)row_bytes);
-    for (int u = threadIdx.x; u < nchunk * kLanes; u += 256) {
-        int c = u / kLanes, lane = u % kLanes;
+    const int nchunk = (row_bytes - tail_bytes) / 16;
+    const unsigned* src = reinterpret_cast<const unsigned*>(blocks + (size_t)b * kLanes * (size_t)row_bytes);
+    for (int u = threadIdx.x; u < nchunk * kLanes * 4; u += 256) {
+        int c = u / (kLanes * 4), lane = (u / 4) % kLanes, wd = u % 4;
         if (b * kLanes + lane < len)
-            *reinterpret_cast<u4*>(dst_rows + (size_t)(b * kLanes + lane) * row_bytes + (size_t)c * 16) = src[u];
+            *reinterpret_cast<unsigned*>(dst_rows + (size_t)(b * kLanes + lane) * row_bytes + (size_t)c * 16 + wd * 4) = src[u];
+    }
+    const unsigned* tails = src + (size_t)nchunk * kLanes * 4;
+    const int tw = tail_bytes / 4;
+    for (int u = threadIdx.x; u < kLanes * tw; u += 256) {
+        int lane = u / tw, wd = u % tw;
+        if (b * kLanes + lane < len)
+            *reinterpret_cast<unsigned*>(dst_rows + (size_t)(b * kLanes + lane) * row_bytes + (row_bytes - tail_bytes) + wd * 4) = tails[u];
     }
 }
 

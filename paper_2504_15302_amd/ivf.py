@@ -17,7 +17,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libivf_mi355x.so")
 
-IVF_FP32, IVF_FP16 = 0, 1
+IVF_FP32, IVF_FP16, IVF_INT8 = 0, 1, 2
 STAGES = ("coarse", "probe", "regroup", "scan", "stream", "select", "total")
 
 EXPORTS = (
@@ -154,7 +154,9 @@ def _dtype_code(a) -> int:
         return IVF_FP32
     if name.endswith("float16"):
         return IVF_FP16
-    raise TypeError(f"vectors must be float32 or float16, got {a.dtype}")
+    if name.endswith("uint8"):          # int8 records: d codes + fp32 scale per row
+        return IVF_INT8
+    raise TypeError(f"vectors must be float32, float16 or uint8 records, got {a.dtype}")
 
 
 class Index:
@@ -181,9 +183,11 @@ class Index:
     def upload(self, centroids, vectors, ids, list_offsets):
         nlist, d = centroids.shape
         n = vectors.shape[0]
-        assert vectors.shape[1] == d and ids.shape[0] == n and list_offsets.shape[0] == nlist + 1
+        dt = _dtype_code(vectors)
+        assert vectors.shape[1] == (d + 4 if dt == IVF_INT8 else d)
+        assert ids.shape[0] == n and list_offsets.shape[0] == nlist + 1
         _check(self._lib.ivf_index_upload(self._h, d, nlist, n, _ptr(centroids), _ptr(vectors),
-                                          _dtype_code(vectors), _ptr(ids), _ptr(list_offsets)))
+                                          dt, _ptr(ids), _ptr(list_offsets)))
 
     def upload_begin(self, centroids, n: int, dtype: int, list_offsets):
         nlist, d = centroids.shape
@@ -253,7 +257,10 @@ class Index:
     def read_list(self, list_no: int, d: int, dtype: int):
         ln = C.c_int64()
         _check(self._lib.ivf_debug_read_list(self._h, list_no, None, None, C.byref(ln)))
-        vec = np.empty((ln.value, d), dtype=np.float16 if dtype == IVF_FP16 else np.float32)
+        if dtype == IVF_INT8:
+            vec = np.empty((ln.value, d + 4), dtype=np.uint8)
+        else:
+            vec = np.empty((ln.value, d), dtype=np.float16 if dtype == IVF_FP16 else np.float32)
         ids = np.empty(ln.value, dtype=np.int64)
         _check(self._lib.ivf_debug_read_list(self._h, list_no, _ptr(vec), _ptr(ids), C.byref(ln)))
         return vec, ids

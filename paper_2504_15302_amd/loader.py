@@ -31,7 +31,7 @@ def load_workload(w: W.Workload, groups_per_chunk: int = 16, log=None) -> Loaded
     cen_dev = torch.from_numpy(cen).cuda()
     ids_dev = W.user_ids_device(w)
     index = ivf.Index()
-    dt = ivf.IVF_FP16 if w.storage == "fp16" else ivf.IVF_FP32
+    dt = {"fp32": ivf.IVF_FP32, "fp16": ivf.IVF_FP16, "int8": ivf.IVF_INT8}[w.storage]
     index.upload_begin(cen, w.n, dt, off)
     last = t0
     for l0, l1, vec in W.iter_device_chunks(w, cen_dev, off, groups_per_chunk):

@@ -104,7 +104,8 @@ class DeviceWorkload:
         coff = np.zeros(len(lists) + 1, dtype=np.int64)
         np.cumsum([lens[l] for l in lists], out=coff[1:])
         vec = np.concatenate([parts[l] for l in lists], axis=0) if lists else \
-            np.empty((0, self.w.d), dtype=np.float16 if self.w.storage == "fp16" else np.float32)
+            np.empty((0, self.w.row_bytes // self.w.elem_bytes if self.w.storage != "int8" else self.w.d + 4),
+                     dtype={"fp32": np.float32, "fp16": np.float16, "int8": np.uint8}[self.w.storage])
         ids = np.concatenate([idp[l] for l in lists]) if lists else np.empty(0, np.int64)
         cmap = {l: i for i, l in enumerate(lists)}
         return vec, ids, coff, cmap
