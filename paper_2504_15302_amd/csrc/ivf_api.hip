@@ -1,331 +1,10 @@
 // Host side of the IVF retrieval library: index storage, placement between HBM and
 // pinned host memory, and the per-search launch sequence.  Exports the C ABI declared
 // in include/ivf.h.
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
-#include <cstdarg>
-#include <cstdio>
-#include <cstring>
-#include <deque>
-#include <limits>
-#include <map>
-#include <new>
-#include <numeric>
-#include <string>
-#include <vector>
-
-#include "../../include/ivf.h"
-#include "ivf_coarse.h"
-#include "ivf_device.h"
-#include "ivf_regroup.h"
-#include "ivf_scan.h"
-#include "ivf_select.h"
-
-extern "C" int ivf_internal_sort_pairs(const int64_t* keys_in, int64_t* keys_out,
-                                       const uint32_t* vals_in, uint32_t* vals_out, size_t n,
-                                       hipStream_t stream);
+#include "ivf_host.h"
+#include "ivf_moves.h"
 
 namespace {
-
-using namespace ivf;
-
-thread_local std::string g_err;
-
-int fail(int code, const char* fmt, ...) {
-    char buf[512];
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
-    va_end(ap);
-    g_err = buf;
-    return code;
-}
-
-#define HIP_TRY(expr)                                                                      \
-    do {                                                                                   \
-        hipError_t e_ = (expr);                                                            \
-        if (e_ != hipSuccess) {                                                            \
-            (void)hipGetLastError();                                                       \
-            return fail(e_ == hipErrorOutOfMemory ? IVF_ERR_OOM_DEVICE : IVF_ERR_HIP,      \
-                        "%s failed: %s", #expr, hipGetErrorString(e_));                    \
-        }                                                                                  \
-    } while (0)
-
-bool is_device_ptr(const void* p) {
-    hipPointerAttribute_t a;
-    hipError_t e = hipPointerGetAttributes(&a, p);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();   // plain host memory is reported as an error
-        return false;
-    }
-    return a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged ||
-           a.type == hipMemoryTypeUnified;
-}
-
-template <class T>
-void dfree(T*& p) {
-    if (p) (void)hipFree(p);
-    p = nullptr;
-}
-
-struct Scratch {
-    size_t cap_q_nlist = 0, cap_q_ntile = 0, cap_pairs = 0, cap_blocks = 0, cap_stream_items = 0;
-    int64_t cap_nlist = 0;
-    float* S = nullptr;
-    float* tmax = nullptr;
-    int32_t* probes = nullptr;
-    int* zeroed = nullptr;          // hist[nlist] | cursor[nlist] | queue[16] | counters (8 x u64) | qthr (nq x u64)
-    unsigned long long* qthr = nullptr;   // per query: running lower bounds of its k-th best score
-    size_t cap_zero_q = 0;
-    uint32_t* wg_totals = nullptr;
-    uint32_t* pair_start = nullptr;
-    uint32_t* sblk_start = nullptr;
-    uint32_t* item_start = nullptr;
-    unsigned long long* counters = nullptr;
-    uint32_t* pair_flat = nullptr;
-    uint32_t* pair_of_probe = nullptr;
-    ScanItem* items = nullptr;
-    ScanItem* stream_items = nullptr;
-    float* scores = nullptr;
-    float* bmax = nullptr;
-    // pinned host mirrors for the streamed path
-    int32_t* h_probes = nullptr;
-    size_t h_probes_cap = 0;
-    ScanItem* h_items = nullptr;
-    size_t h_items_cap = 0;
-    unsigned long long* h_counters = nullptr;
-    size_t bytes = 0;
-};
-
-constexpr int kMaxStage = 8;
-constexpr int kMaxSide = 4;
-constexpr int kTimingSlots = 64;   // searches whose stage events are kept
-constexpr int kEvPerSearch = 7;    // stage boundaries 0..6
-
-// List data lives in pools of fixed-size segments (one hipMalloc / hipHostMalloc each),
-// carved in units of one 64-vector block.  A list is contiguous inside one segment.
-// Segments let a change of the device budget move only the lists that change tier and
-// hand memory back segment by segment, without ever holding a second copy of a tier.
-struct Seg {
-    char* base = nullptr;
-    size_t blocks = 0, used = 0;
-    std::map<size_t, size_t> free;   // offset -> length, in blocks, coalesced
-};
-struct Pool {
-    bool device = true;
-    size_t block_bytes = 0, seg_blocks = 0;
-    std::vector<Seg> segs;           // a dropped segment keeps its slot (base == nullptr)
-    size_t allocated_blocks() const {
-        size_t n = 0;
-        for (const Seg& g : segs) n += g.blocks;
-        return n;
-    }
-};
-struct Loc {
-    int8_t tier = 0;                 // 0 = HBM, 1 = pinned host
-    int32_t seg = -1;                // -1: the list is empty
-    size_t off = 0;                  // in blocks
-};
-
-// A change of the device budget is a sequence of list moves (HBM -> host, HBM -> HBM while
-// the pool is compacted, host -> HBM), copied in batches on a stream of their own while
-// searches go on.  A list keeps being read at its old place until its copy has landed and
-// the new address table has reached the device; the old place is released only after
-// every search that may still read it has finished.
-struct Move {
-    int32_t l = 0;
-    Loc from, to;
-    bool placed = false;             // destination already reserved (compaction)
-};
-struct MoveBatch {
-    hipEvent_t landed = nullptr;     // recorded on the move stream behind the batch's copies
-    std::vector<Move> moves;
-    size_t bytes = 0;
-};
-struct Limbo {
-    hipEvent_t after = nullptr;      // recorded behind the table update that retires the old places
-    const void** table = nullptr;    // pinned snapshot of the address table that the update copies
-    std::vector<Move> moves;         // their `from` places are released once `after` has completed
-};
-enum { kPhaseIdle = 0, kPhaseEvict = 1, kPhaseCompact = 2, kPhaseLoad = 3 };
-
-}  // namespace
-
-struct ivf_index {
-    int device = 0;
-    int cus = 256;
-    bool uploading = false, ready = false;
-    int d = 0, dtype = 0, es = 4;
-    int64_t nlist = 0, n = 0, next_list = 0;
-    size_t row_bytes = 0, block_bytes = 0;      // one stored vector as uploaded; 64 of them, blocked
-    int tail_bytes = 0;                         // bytes of a row behind its d elements (int8: the scale)
-    int64_t total_blocks = 0, max_len = 0;
-    std::vector<int64_t> offsets, blk_off;
-    std::vector<int32_t> len, nblk;
-    std::vector<int64_t> top_nblk_prefix;       // prefix sums of nblk sorted descending
-    std::vector<const char*> dev_ptr, host_ptr; // per list: where its blocks live (derived from loc)
-    std::vector<Loc> loc;
-    Pool dpool, hpool;
-    // device tables
-    float* d_centroids = nullptr;
-    int64_t* d_offsets = nullptr;
-    int32_t* d_len = nullptr;
-    int32_t* d_nblk = nullptr;
-    const void** d_list_ptr = nullptr;
-    int64_t* d_ids_pos = nullptr;      // only while uploading
-    int64_t* d_id_sorted = nullptr;
-    uint32_t* d_rank_of_pos = nullptr;
-    uint32_t* d_hits = nullptr;        // per list: how often it has been probed (residency policy)
-    int64_t resident_lists = 0;
-    int64_t moved_h2d = 0, moved_d2h = 0, moved_d2d = 0;   // bytes moved by the last budget change
-    // budget change in progress
-    int phase = kPhaseIdle;
-    bool compact_wanted = false;
-    std::deque<Move> todo;             // moves of the current phase that have not been issued
-    std::deque<MoveBatch> inflight;    // issued, copy not yet known to have landed
-    std::deque<Limbo> limbo;           // landed and switched over, old places not yet released
-    std::vector<int32_t> to_load;      // lists to bring into HBM once evictions and compaction are over
-    std::vector<char> seg_skip;        // HBM segments that compaction could not empty
-    size_t inflight_bytes = 0;
-    int64_t pending_lists = 0, pending_bytes = 0;   // lists that still have to change tier
-    int move_rc = 0;                   // why the last change stopped early (0: it did not)
-    std::string move_msg;
-    hipStream_t move_stream = nullptr, patch_stream = nullptr;
-    hipEvent_t ev_search_end = nullptr;
-    bool search_end_recorded = false;
-    std::vector<hipEvent_t> spare_events;
-    std::vector<const void**> spare_tables;
-    const void** h_list_ptr = nullptr; // pinned host mirror of d_list_ptr
-    // streaming of host-resident lists
-    hipStream_t side[kMaxSide] = {};   // copy streams for host-resident lists (chunks alternate)
-    char* stage[kMaxStage] = {};
-    hipEvent_t stage_ready[kMaxStage] = {}, stage_free[kMaxStage] = {};
-    bool stage_used[kMaxStage] = {};
-    size_t stage_bytes = 0;
-    int nstage = 0;
-    hipEvent_t ev_probes = nullptr, ev_done = nullptr;
-    bool done_recorded = false;
-    // search state
-    Scratch sc;
-    int prune_blocks = 0, prune_j = 0;   // bound kept by the scan for the current search (see k_scan)
-    int last_nq = 0, last_nprobe = 0;
-    hipStream_t last_stream = nullptr;
-    bool last_offload = false;
-    ivf_search_stats last_stats = {};
-    bool timing = false;
-    hipEvent_t ev[kTimingSlots][kEvPerSearch] = {};
-    bool ev_created = false;
-    int64_t timed_searches = 0;        // searches recorded since timing was switched on
-    // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
-            opt_nstage = 3, opt_move_chunk_kb = 64 << 10, opt_move_inflight_kb = 4 << 20;
-};
-
-namespace {
-
-void pool_free_all(Pool& p) {
-    for (Seg& g : p.segs)
-        if (g.base) { if (p.device) (void)hipFree(g.base); else (void)hipHostFree(g.base); }
-    p.segs.clear();
-}
-
-// New segment of `blocks` blocks; returns its index or -1 when the allocation fails.
-int pool_new_seg(Pool& p, size_t blocks) {
-    char* base = nullptr;
-    const size_t bytes = blocks * p.block_bytes;
-    hipError_t e = p.device ? hipMalloc(reinterpret_cast<void**>(&base), bytes)
-                            : hipHostMalloc(reinterpret_cast<void**>(&base), bytes);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        return -1;
-    }
-    int idx = -1;
-    for (size_t i = 0; i < p.segs.size(); ++i)
-        if (!p.segs[i].base) { idx = (int)i; break; }
-    if (idx < 0) { p.segs.emplace_back(); idx = (int)p.segs.size() - 1; }
-    Seg& g = p.segs[idx];
-    g.base = base; g.blocks = blocks; g.used = 0;
-    g.free.clear();
-    g.free[0] = blocks;
-    return idx;
-}
-
-// First fit over the existing segments (skipping `exclude`), then a new segment if allowed.
-bool pool_alloc(Pool& p, size_t n, int& seg, size_t& off, bool may_grow, int exclude = -1) {
-    for (size_t i = 0; i < p.segs.size(); ++i) {
-        Seg& g = p.segs[i];
-        if (!g.base || (int)i == exclude || g.blocks - g.used < n) continue;
-        for (auto it = g.free.begin(); it != g.free.end(); ++it) {
-            if (it->second < n) continue;
-            const size_t o = it->first, len = it->second;
-            g.free.erase(it);
-            if (len > n) g.free[o + n] = len - n;
-            g.used += n;
-            seg = (int)i; off = o;
-            return true;
-        }
-    }
-    if (!may_grow) return false;
-    int idx = pool_new_seg(p, std::max(p.seg_blocks, n));
-    if (idx < 0 && p.seg_blocks > n) idx = pool_new_seg(p, n);
-    if (idx < 0) return false;
-    Seg& g = p.segs[idx];
-    g.free.clear();
-    if (g.blocks > n) g.free[n] = g.blocks - n;
-    g.used = n;
-    seg = idx; off = 0;
-    return true;
-}
-
-void pool_release(Pool& p, int seg, size_t off, size_t n) {
-    Seg& g = p.segs[seg];
-    auto it = g.free.emplace(off, n).first;
-    auto nx = std::next(it);
-    if (nx != g.free.end() && it->first + it->second == nx->first) {
-        it->second += nx->second;
-        g.free.erase(nx);
-    }
-    if (it != g.free.begin()) {
-        auto pv = std::prev(it);
-        if (pv->first + pv->second == it->first) {
-            pv->second += it->second;
-            g.free.erase(it);
-        }
-    }
-    g.used -= n;
-}
-
-void pool_drop_empty(Pool& p) {
-    for (Seg& g : p.segs)
-        if (g.base && g.used == 0) {
-            if (p.device) (void)hipFree(g.base); else (void)hipHostFree(g.base);
-            g = Seg();
-        }
-}
-
-// Where list l is read from, as the host sees it (dev_ptr / host_ptr) and as the device
-// table will see it (h_list_ptr: a host-resident list has a null entry, or — when the scan
-// is to read pinned host memory directly — its host address tagged in bit 0).
-void set_list_entry(ivf_index* x, int64_t l) {
-    const Loc& c = x->loc[l];
-    x->dev_ptr[l] = x->host_ptr[l] = nullptr;
-    if (c.seg < 0) {         // empty list: a non-null device address marks it resident
-        if (c.tier == 0) x->dev_ptr[l] = reinterpret_cast<const char*>(x->d_centroids);
-    } else {
-        const Pool& p = c.tier == 0 ? x->dpool : x->hpool;
-        const char* a = p.segs[c.seg].base + c.off * p.block_bytes;
-        (c.tier == 0 ? x->dev_ptr : x->host_ptr)[l] = a;
-    }
-    const char* t = x->dev_ptr[l];
-    if (!t && x->host_ptr[l] && x->opt_host_direct)
-        t = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(x->host_ptr[l]) | 1u);
-    x->h_list_ptr[l] = t;
-}
-
-void refresh_list_ptrs(ivf_index* x) {
-    for (int64_t l = 0; l < x->nlist; ++l) set_list_entry(x, l);
-}
 
 void free_scratch(Scratch& s) {
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
@@ -346,54 +25,6 @@ void free_staging(ivf_index* x) {
     }
     x->nstage = 0;
     x->stage_bytes = 0;
-}
-
-hipEvent_t take_event(ivf_index* x) {
-    if (!x->spare_events.empty()) {
-        hipEvent_t e = x->spare_events.back();
-        x->spare_events.pop_back();
-        return e;
-    }
-    hipEvent_t e = nullptr;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    return e;
-}
-
-const void** take_table(ivf_index* x) {
-    if (!x->spare_tables.empty()) {
-        const void** t = x->spare_tables.back();
-        x->spare_tables.pop_back();
-        return t;
-    }
-    const void** t = nullptr;
-    if (hipHostMalloc(reinterpret_cast<void**>(&t), sizeof(void*) * (size_t)x->nlist) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    return t;
-}
-
-// Forgets a budget change in progress.  Only for an idle device whose pools are about to be
-// freed as a whole: nothing is released list by list.
-void moves_reset(ivf_index* x) {
-    for (MoveBatch& b : x->inflight)
-        if (b.landed) x->spare_events.push_back(b.landed);
-    for (Limbo& lb : x->limbo) {
-        if (lb.after) x->spare_events.push_back(lb.after);
-        if (lb.table) x->spare_tables.push_back(lb.table);
-    }
-    x->inflight.clear(); x->limbo.clear(); x->todo.clear(); x->to_load.clear(); x->seg_skip.clear();
-    for (const void** t : x->spare_tables) (void)hipHostFree(t);   // sized for the index that goes away
-    x->spare_tables.clear();
-    x->phase = kPhaseIdle;
-    x->inflight_bytes = 0;
-    x->pending_lists = x->pending_bytes = 0;
-    x->move_rc = 0;
-    x->move_msg.clear();
-    x->search_end_recorded = false;
 }
 
 void free_index_data(ivf_index* x) {
@@ -424,15 +55,6 @@ int dalloc(T*& p, size_t count, size_t& total) {
     return 0;
 }
 
-// Device table of list addresses, copied from its host mirror (synchronous).
-int upload_list_ptr_table(ivf_index* x) {
-    refresh_list_ptrs(x);
-    HIP_TRY(hipMemcpy(x->d_list_ptr, x->h_list_ptr, sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice));
-    return 0;
-}
-
-// Upper bound on score blocks (and scan items) of a batch: every query probing the
-// nprobe longest lists.
 int64_t block_bound(const ivf_index* x, int64_t nq, int nprobe) {
     size_t p = std::min<size_t>((size_t)nprobe, x->top_nblk_prefix.size() - 1);
     return nq * x->top_nblk_prefix[p];
@@ -684,280 +306,6 @@ int check_ready(const ivf_index* x) {
 }
 
 
-// ---- budget changes as a background activity -------------------------------------------
-
-bool moves_active(const ivf_index* x) {
-    return x->phase != kPhaseIdle || !x->inflight.empty() || !x->limbo.empty();
-}
-
-char* loc_addr(ivf_index* x, const Loc& c) {
-    Pool& p = c.tier == 0 ? x->dpool : x->hpool;
-    return p.segs[c.seg].base + c.off * p.block_bytes;
-}
-
-void release_place(ivf_index* x, const Loc& c, int32_t l) {
-    pool_release(c.tier == 0 ? x->dpool : x->hpool, c.seg, c.off, (size_t)x->nblk[l]);
-}
-
-// Ends a change early: what has not been issued is dropped (reserved places are handed
-// back).  Copies already issued still land and are committed by moves_advance.
-void moves_stop(ivf_index* x, int rc, const std::string& msg) {
-    for (const Move& m : x->todo)
-        if (m.placed) release_place(x, m.to, m.l);
-    x->todo.clear();
-    x->to_load.clear();
-    x->phase = kPhaseIdle;
-    if (rc) {
-        x->move_rc = rc;
-        x->move_msg = msg;
-    }
-}
-
-// Sends the address table to the device behind the searches issued so far (the copy reads
-// a snapshot, so a later change of the mirror cannot reach an earlier search) and parks
-// the old places of `lb` until that has happened.
-int push_table(ivf_index* x, Limbo& lb) {
-    std::memcpy(lb.table, x->h_list_ptr, sizeof(void*) * (size_t)x->nlist);
-    if (x->search_end_recorded) HIP_TRY(hipStreamWaitEvent(x->patch_stream, x->ev_search_end, 0));
-    HIP_TRY(hipMemcpyAsync(x->d_list_ptr, lb.table, sizeof(void*) * (size_t)x->nlist, hipMemcpyHostToDevice, x->patch_stream));
-    HIP_TRY(hipEventRecord(lb.after, x->patch_stream));
-    x->limbo.push_back(std::move(lb));
-    return 0;
-}
-
-// Compaction of the HBM pool: picks the least-filled segment whose lists fit into the
-// holes of the other segments, reserves those holes and queues the device-to-device moves.
-bool compact_pick(ivf_index* x) {
-    Pool& p = x->dpool;
-    std::vector<int> segs;
-    size_t total_free = 0;
-    for (size_t i = 0; i < p.segs.size(); ++i) {
-        if (!p.segs[i].base) continue;
-        total_free += p.segs[i].blocks - p.segs[i].used;
-        if (p.segs[i].used > 0 && !(i < x->seg_skip.size() && x->seg_skip[i])) segs.push_back((int)i);
-    }
-    std::sort(segs.begin(), segs.end(), [&](int a, int b) { return p.segs[a].used < p.segs[b].used; });
-    for (int sidx : segs) {
-        const Seg& g = p.segs[sidx];
-        if (total_free - (g.blocks - g.used) < g.used) continue;
-        std::vector<int32_t> lists;
-        for (int64_t l = 0; l < x->nlist; ++l)
-            if (x->loc[l].tier == 0 && x->loc[l].seg == sidx) lists.push_back((int32_t)l);
-        if (lists.empty()) continue;
-        std::sort(lists.begin(), lists.end(), [&](int32_t a, int32_t b) {
-            return x->nblk[a] != x->nblk[b] ? x->nblk[a] > x->nblk[b] : a < b;     // large lists first: first fit packs better
-        });
-        std::vector<Move> mv;
-        bool ok = true;
-        for (int32_t l : lists) {
-            Move m;
-            m.l = l; m.from = x->loc[l]; m.to.tier = 0; m.placed = true;
-            if (!pool_alloc(p, (size_t)x->nblk[l], m.to.seg, m.to.off, false, sidx)) { ok = false; break; }
-            mv.push_back(m);
-        }
-        if (!ok) {                                   // holes too small: leave this segment alone
-            for (const Move& m : mv) release_place(x, m.to, m.l);
-            if ((size_t)sidx < x->seg_skip.size()) x->seg_skip[sidx] = 1;
-            continue;
-        }
-        for (const Move& m : mv) x->todo.push_back(m);
-        return true;
-    }
-    return false;
-}
-
-// The current phase has nothing left to issue, in flight or in limbo: go on to the next.
-void next_phase(ivf_index* x) {
-    if (x->phase == kPhaseEvict) {
-        x->phase = kPhaseCompact;
-        x->seg_skip.assign(x->dpool.segs.size(), 0);
-    }
-    if (x->phase == kPhaseCompact) {
-        pool_drop_empty(x->dpool);                   // the segment emptied last, if any
-        if (x->compact_wanted && compact_pick(x)) return;
-        x->phase = kPhaseLoad;
-        for (int32_t l : x->to_load) {
-            Move m;
-            m.l = l; m.from = x->loc[l]; m.to.tier = 0;
-            x->todo.push_back(m);
-        }
-        x->to_load.clear();
-        if (!x->todo.empty()) return;
-    }
-    pool_drop_empty(x->hpool);
-    x->phase = kPhaseIdle;
-}
-
-// One non-blocking step of the change in progress: releases old places whose readers are
-// done, switches over the lists whose copies have landed, issues further copies.
-int moves_advance(ivf_index* x) {
-    while (!x->limbo.empty()) {
-        Limbo& lb = x->limbo.front();
-        hipError_t q = hipEventQuery(lb.after);
-        if (q == hipErrorNotReady) { (void)hipGetLastError(); break; }
-        if (q != hipSuccess) { (void)hipGetLastError(); return fail(IVF_ERR_HIP, "list table update failed: %s", hipGetErrorString(q)); }
-        for (const Move& m : lb.moves) release_place(x, m.from, m.l);
-        x->spare_events.push_back(lb.after);
-        x->spare_tables.push_back(lb.table);
-        x->limbo.pop_front();
-    }
-    {
-        Limbo lb;
-        while (!x->inflight.empty()) {
-            MoveBatch& b = x->inflight.front();
-            hipError_t q = hipEventQuery(b.landed);
-            if (q == hipErrorNotReady) { (void)hipGetLastError(); break; }
-            if (q != hipSuccess) { (void)hipGetLastError(); return fail(IVF_ERR_HIP, "moving lists failed: %s", hipGetErrorString(q)); }
-            if (!lb.after) {
-                lb.after = take_event(x);
-                lb.table = take_table(x);
-                if (!lb.after || !lb.table) {
-                    if (lb.after) x->spare_events.push_back(lb.after);
-                    if (lb.table) x->spare_tables.push_back(lb.table);
-                    return fail(IVF_ERR_OOM_HOST, "no event or pinned table for a list table update");
-                }
-            }
-            for (const Move& m : b.moves) {
-                x->loc[m.l] = m.to;
-                set_list_entry(x, m.l);
-                const int64_t by = (int64_t)((size_t)x->nblk[m.l] * x->block_bytes);
-                if (m.from.tier == 0 && m.to.tier == 1) { x->moved_d2h += by; x->resident_lists -= 1; }
-                else if (m.from.tier == 1 && m.to.tier == 0) { x->moved_h2d += by; x->resident_lists += 1; }
-                else x->moved_d2d += by;
-                lb.moves.push_back(m);
-            }
-            x->inflight_bytes -= b.bytes;
-            x->spare_events.push_back(b.landed);
-            x->inflight.pop_front();
-        }
-        if (lb.after) {
-            int rc = push_table(x, lb);
-            if (rc) return rc;
-        }
-    }
-    const size_t chunk = (size_t)x->opt_move_chunk_kb << 10, cap = (size_t)x->opt_move_inflight_kb << 10;
-    while (x->phase != kPhaseIdle) {
-        if (x->todo.empty()) {
-            if (!x->inflight.empty() || !x->limbo.empty()) break;
-            next_phase(x);
-            continue;
-        }
-        if (x->inflight_bytes >= cap) break;
-        MoveBatch b;
-        b.landed = take_event(x);
-        if (!b.landed) { moves_stop(x, IVF_ERR_HIP, "no event for a batch of list copies"); break; }
-        while (!x->todo.empty() && b.bytes < chunk && x->inflight_bytes + b.bytes < cap) {
-            Move m = x->todo.front();
-            const size_t nb = (size_t)x->nblk[m.l];
-            if (!m.placed && !pool_alloc(m.to.tier == 0 ? x->dpool : x->hpool, nb, m.to.seg, m.to.off, true)) {
-                char msg[128];
-                std::snprintf(msg, sizeof msg, "out of %s memory while moving list %d", m.to.tier == 0 ? "device" : "pinned host", m.l);
-                moves_stop(x, m.to.tier == 0 ? IVF_ERR_OOM_DEVICE : IVF_ERR_OOM_HOST, msg);
-                break;
-            }
-            x->todo.pop_front();
-            hipError_t e = hipMemcpyAsync(loc_addr(x, m.to), loc_addr(x, m.from), nb * x->block_bytes, hipMemcpyDefault, x->move_stream);
-            if (e != hipSuccess) {
-                (void)hipGetLastError();
-                release_place(x, m.to, m.l);
-                moves_stop(x, IVF_ERR_HIP, std::string("copy of a list failed: ") + hipGetErrorString(e));
-                break;
-            }
-            b.moves.push_back(m);
-            b.bytes += nb * x->block_bytes;
-        }
-        if (b.moves.empty()) { x->spare_events.push_back(b.landed); break; }
-        hipError_t e = hipEventRecord(b.landed, x->move_stream);
-        if (e != hipSuccess) {
-            // the copies cannot be tracked: wait for them here, the batch then counts as landed
-            (void)hipGetLastError();
-            (void)hipStreamSynchronize(x->move_stream);
-            (void)hipEventRecord(b.landed, x->move_stream);
-        }
-        x->inflight_bytes += b.bytes;
-        x->inflight.push_back(std::move(b));
-    }
-    return 0;
-}
-
-// Blocks until no change is in progress.  With `cancel`, what has not been issued is dropped.
-int moves_drain(ivf_index* x, bool cancel) {
-    if (cancel && x->phase != kPhaseIdle) moves_stop(x, 0, "");
-    while (moves_active(x)) {
-        int rc = moves_advance(x);
-        if (rc) return rc;
-        if (!x->inflight.empty()) HIP_TRY(hipEventSynchronize(x->inflight.front().landed));
-        else if (!x->limbo.empty()) HIP_TRY(hipEventSynchronize(x->limbo.front().after));
-    }
-    return 0;
-}
-
-// Works out which lists have to change tier for a budget of `bytes` and queues the change.
-// The device is idle and no change is in progress.
-int budget_plan(ivf_index* x, int64_t bytes) {
-    const int64_t nlist = x->nlist;
-    x->moved_h2d = x->moved_d2h = x->moved_d2d = 0;
-    x->move_rc = 0;
-    x->move_msg.clear();
-    x->search_end_recorded = false;
-    // which lists are to be resident: ranked by the policy, while they fit
-    std::vector<uint32_t> hits;
-    if (x->opt_policy == 1) {
-        hits.resize((size_t)nlist);
-        HIP_TRY(hipMemcpy(hits.data(), x->d_hits, sizeof(uint32_t) * (size_t)nlist, hipMemcpyDeviceToHost));
-    }
-    std::vector<int32_t> order((size_t)nlist);
-    std::iota(order.begin(), order.end(), 0);
-    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-        if (!hits.empty() && hits[a] != hits[b]) return hits[a] > hits[b];
-        if (x->len[a] != x->len[b]) return x->len[a] > x->len[b];
-        return a < b;
-    });
-    std::vector<char> res((size_t)nlist, 0);
-    uint64_t used = 0;
-    for (int32_t l : order) {
-        uint64_t b = (uint64_t)x->nblk[l] * x->block_bytes;
-        if (used + b > (uint64_t)bytes) break;
-        used += b;
-        res[l] = 1;
-    }
-    // evictions go least valuable first, loads most valuable first; a list without data
-    // just changes its label
-    bool relabelled = false;
-    for (auto it = order.rbegin(); it != order.rend(); ++it) {
-        const int32_t l = *it;
-        if (x->loc[l].tier != 0 || res[l]) continue;
-        if (x->nblk[l] == 0) { x->loc[l].tier = 1; x->resident_lists -= 1; relabelled = true; continue; }
-        Move m;
-        m.l = l; m.from = x->loc[l]; m.to.tier = 1;
-        x->todo.push_back(m);
-    }
-    for (int32_t l : order) {
-        if (x->loc[l].tier != 1 || !res[l]) continue;
-        if (x->nblk[l] == 0) { x->loc[l].tier = 0; x->resident_lists += 1; relabelled = true; continue; }
-        x->to_load.push_back(l);
-    }
-    if (relabelled) {
-        int rc = upload_list_ptr_table(x);
-        if (rc) return rc;
-    }
-    if (x->todo.empty() && x->to_load.empty()) return 0;
-    x->compact_wanted = !x->todo.empty();
-    x->phase = kPhaseEvict;
-    return 0;
-}
-
-void count_pending(const ivf_index* x, int64_t& lists, int64_t& bytes) {
-    lists = bytes = 0;
-    auto add = [&](int32_t l) { lists += 1; bytes += (int64_t)((size_t)x->nblk[l] * x->block_bytes); };
-    for (const MoveBatch& b : x->inflight)
-        for (const Move& m : b.moves)
-            if (m.from.tier != m.to.tier) add(m.l);
-    for (const Move& m : x->todo)
-        if (m.from.tier != m.to.tier) add(m.l);
-    for (int32_t l : x->to_load) add(l);
-}
-
 }  // namespace
 
 extern "C" {
@@ -1090,7 +438,8 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
         size_t max_nb = 1;
         for (int64_t l = 0; l < nlist; ++l) max_nb = std::max<size_t>(max_nb, (size_t)x->nblk[l]);
         x->dpool = Pool(); x->hpool = Pool();
-        x->dpool.device = true; x->hpool.device = false;
+        x->dpool.alloc = hbm_alloc; x->dpool.dealloc = hbm_free;
+        x->hpool.alloc = pinned_alloc; x->hpool.dealloc = pinned_free;
         x->dpool.block_bytes = x->hpool.block_bytes = x->block_bytes;
         x->dpool.seg_blocks = x->hpool.seg_blocks = std::max<size_t>(max_nb, seg_bytes / x->block_bytes);
         size_t left = (size_t)x->total_blocks;
