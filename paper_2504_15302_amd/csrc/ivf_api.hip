@@ -415,7 +415,9 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
     }
     size_t tot = 0;
     int rc;
-    if ((rc = dalloc(x->d_centroids, (size_t)nlist * d, tot))) return rc;
+    const int cstep = (d + kCoarseKT - 1) / kCoarseKT;
+    const size_t ctiles = ((size_t)nlist + 31) / 32;
+    if ((rc = dalloc(x->d_centroids, ctiles * cstep * 1024, tot))) return rc;    // tiled for k_coarse
     if ((rc = dalloc(x->d_offsets, (size_t)nlist + 1, tot))) return rc;
     if ((rc = dalloc(x->d_len, (size_t)nlist, tot))) return rc;
     if ((rc = dalloc(x->d_nblk, (size_t)nlist, tot))) return rc;
@@ -458,7 +460,21 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
         }
         x->dpool.seg_blocks = x->hpool.seg_blocks;
     }
-    HIP_TRY(hipMemcpy(x->d_centroids, centroids, sizeof(float) * (size_t)nlist * d, hipMemcpyDefault));
+    {
+        float* raw = nullptr;
+        size_t unused = 0;
+        if ((rc = dalloc(raw, (size_t)nlist * d, unused))) return rc;
+        hipError_t e = hipMemcpy(raw, centroids, sizeof(float) * (size_t)nlist * d, hipMemcpyDefault);
+        if (e == hipSuccess) {
+            const size_t nv = ctiles * cstep * 256;
+            hipLaunchKernelGGL(k_tile_centroids, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, 0, raw, x->d_centroids,
+                               (int)nlist, d, cstep, nv);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hipDeviceSynchronize();
+        }
+        dfree(raw);
+        HIP_TRY(e);
+    }
     HIP_TRY(hipMemcpy(x->d_offsets, x->offsets.data(), sizeof(int64_t) * ((size_t)nlist + 1), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_len, x->len.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(x->d_nblk, x->nblk.data(), sizeof(int32_t) * (size_t)nlist, hipMemcpyHostToDevice));
