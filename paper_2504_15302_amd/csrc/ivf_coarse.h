@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
                                                 const float* __restrict__ Ct,
                                                 float* __restrict__ S, float* __restrict__ tmax,
                                                 int nq, int nlist, int d, int ntile) {
-    __shared__ float qs[MT * 32 * kCoarseLd];
+    __shared__ float qs[2][MT * 32 * kCoarseLd];     // query tiles of two consecutive steps
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int col = lane & 31;
@@ -88,10 +88,10 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
             qr[i] = *reinterpret_cast<const v4f*>(Q + (size_t)m * d + kk);
         }
     };
-    auto read_a = [&](v4f (&a)[MT], int j) {
+    auto read_a = [&](v4f (&a)[MT], const float* tile, int j) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            a[mt] = *reinterpret_cast<const v4f*>(&qs[(mt * 32 + col) * kCoarseLd + j * 8 + half * 4]);
+            a[mt] = *reinterpret_cast<const v4f*>(&tile[(mt * 32 + col) * kCoarseLd + j * 8 + half * 4]);
     };
     // The centroid operand streams from HBM (every row is read once), whose latency under
     // load exceeds one step of MFMAs: it is fetched two steps ahead, into three register
@@ -102,30 +102,41 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
     // does not also wait for the centroid loads issued in the same step.
     v4f q_reg[MT];
     auto step = [&](v4f (&b_cur)[4], v4f (&b_far)[4], int kb) {
-        __syncthreads();                    // the previous step's LDS reads are done
+        // Two LDS tiles alternate, so one barrier per step is enough: a wavefront that has
+        // passed the barrier of step s has seen every wavefront finish reading the tile of
+        // step s-1, which is the one step s+1 overwrites.
+        float* tile = qs[(kb / kCoarseKT) & 1];
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             int idx = threadIdx.x + i * 256;
             int row = idx >> 3, c4 = idx & 7;
-            *reinterpret_cast<v4f*>(&qs[row * kCoarseLd + c4 * 4]) = q_reg[i];
+            *reinterpret_cast<v4f*>(&tile[row * kCoarseLd + c4 * 4]) = q_reg[i];
         }
         __syncthreads();
         load_q(q_reg, min(kb + kCoarseKT, d - 4));
         load_b(b_far, kb / kCoarseKT + 2);                 // past the end: a harmless reload
         __builtin_amdgcn_sched_barrier(0);   // keep these loads ahead of the MFMAs that hide them
-        v4f a_cur[MT], a_nxt[MT];
-        read_a(a_cur, 0);
+        // LDS reads of the next eight k are issued before the MFMAs of the current eight, in
+        // two alternating register sets; the group barriers below pin that order (left
+        // alone, the scheduler gathers the reads and then waits for them in front of the
+        // matrix instructions).
+        v4f a[2][MT];
+        read_a(a[0], tile, 0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (j < 3) read_a(a_nxt, j + 1);
+            if (j < 3) read_a(a[(j + 1) & 1], tile, j + 1);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[mt][s], b_cur[j][s], acc[mt], 0, 0, 0);
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a_cur[mt] = a_nxt[mt];
+                for (int mt = 0; mt < MT; ++mt)
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j & 1][mt][s], b_cur[j][s], acc[mt], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);     // reads for k 0..15
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * MT, 0);     // MFMAs of k 0..7
+        __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);         // reads for k 16..23
+        __builtin_amdgcn_sched_group_barrier(0x008, 4 * MT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);         // reads for k 24..31
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 * MT, 0);
     };
     v4f b0[4], b1[4], b2[4];
     load_q(q_reg, 0);
