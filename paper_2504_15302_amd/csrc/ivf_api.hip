@@ -706,17 +706,19 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
         hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, s.zeroed, nz);
     }
     {
+        // Query rows per wavefront: as many as possible (each centroid row is then fetched
+        // once), but few enough that the grid still offers every SIMD a wavefront.
         dim3 grid((unsigned)((nlist + kCoarseNT - 1) / kCoarseNT), 1);
-        if (nq <= 32) {
-            grid.y = 1;
+        const int64_t simds = (int64_t)x->cus * 4, waves_x = (int64_t)grid.x * 4;
+        int mt = nq > 64 ? 4 : nq > 32 ? 2 : 1;
+        while (mt > 1 && waves_x * ((nq + 32 * mt - 1) / (32 * mt)) < simds) mt >>= 1;
+        grid.y = (unsigned)((nq + 32 * mt - 1) / (32 * mt));
+        if (mt == 1)
             hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
-        } else if (nq <= 64) {
-            grid.y = 1;
+        else if (mt == 2)
             hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
-        } else {
-            grid.y = (unsigned)((nq + 127) / 128);
+        else
             hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
-        }
     }
     mark();   // 1
     int* hist = s.zeroed;

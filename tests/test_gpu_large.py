@@ -121,6 +121,10 @@ def test_c5_full_size_sampled_rows_match_oracle():
     rows = [0, 17, 63, 64, 101, 127]
     res = check_large(dw, q, w.nprobe, w.k, got, rows=rows)
     say(f"C5 ok on rows {rows}: {res}")
+    # half the batch: the coarse kernel then runs its 64-row tile
+    say("C5: search nq=64 nprobe=16 k=10")
+    got = gpu_search(dw.index, q[:64], 16, 10)
+    res = check_large(dw, q[:64], 16, 10, got, rows=[1, 33, 62])
     _check_assignment_sample(dw, nsample_lists=8)
     _check_readback(dw, [w.nlist - 1])
     info = dw.index.info()
