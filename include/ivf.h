@@ -22,7 +22,7 @@
  *   - One search (or upload, or budget change) at a time per index: calls on the
  *     same index must not overlap.  Different indexes are independent.
  *   - Limits: d a multiple of 8 and d <= 4096; 1 <= k <= 1024; 1 <= nprobe <= 1024
- *     (nprobe above nlist is clamped to nlist); n < 2^32; nlist < 2^31.
+ *     (nprobe above nlist is clamped to nlist); n < 2^32; nlist < 2^28.
  *   - Ordering rule: best first by (score descending, user id ascending, upload
  *     position ascending).  The GPU accumulates scores in fp32.
  */

@@ -372,8 +372,8 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
     if (d <= 0 || nlist <= 0 || n < 0) return fail(IVF_ERR_INVALID, "d, nlist must be positive and n non-negative");
     if (d % 8 != 0 || d > 4096) return fail(IVF_ERR_LIMIT, "d must be a multiple of 8 and at most 4096 (got %d)", d);
     if (dtype == IVF_INT8 && d % 16 != 0) return fail(IVF_ERR_LIMIT, "d must be a multiple of 16 for int8 storage (got %d)", d);
-    if (n >= (int64_t)1 << 32 || nlist >= (int64_t)1 << 31)
-        return fail(IVF_ERR_LIMIT, "n must be below 2^32 and nlist below 2^31");
+    if (n >= (int64_t)1 << 32 || nlist >= (int64_t)1 << 28)
+        return fail(IVF_ERR_LIMIT, "n must be below 2^32 and nlist below 2^28");
     (void)hipDeviceSynchronize();
     free_index_data(x);
     x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : dtype == IVF_INT8 ? 1 : 4;
@@ -701,10 +701,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     auto mark = [&]() { if (tm) (void)hipEventRecord(evs[evi], st); ++evi; };
 
     mark();   // 0
-    {
-        size_t nz = 2 * (size_t)nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq;
-        hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, s.zeroed, nz);
-    }
+    const int nz = (int)(2 * (size_t)nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq);   // cleared by the coarse kernel
     {
         // Query rows per wavefront: as many as possible (each centroid row is then fetched
         // once), but few enough that the grid still offers every SIMD a wavefront.
@@ -714,11 +711,11 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
         while (mt > 1 && waves_x * ((nq + 32 * mt - 1) / (32 * mt)) < simds) mt >>= 1;
         grid.y = (unsigned)((nq + 32 * mt - 1) / (32 * mt));
         if (mt == 1)
-            hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+            hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
         else if (mt == 2)
-            hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+            hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
         else
-            hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile);
+            hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
     }
     mark();   // 1
     int* hist = s.zeroed;

@@ -48,7 +48,12 @@ template <int MT>
 __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
                                                 const float* __restrict__ Ct,
                                                 float* __restrict__ S, float* __restrict__ tmax,
-                                                int nq, int nlist, int d, int ntile) {
+                                                int nq, int nlist, int d, int ntile,
+                                                int* __restrict__ zero, int nzero) {
+    // The search's zero-initialised scratch (probe histogram, cursors, counters, bounds) is
+    // first touched by the kernels after this one: clearing it here saves a launch.
+    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < nzero; i += gridDim.x * gridDim.y * 256)
+        zero[i] = 0;
     __shared__ float qs[2][MT * 32 * kCoarseLd];     // query tiles of two consecutive steps
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
