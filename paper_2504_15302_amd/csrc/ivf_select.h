@@ -2,8 +2,8 @@
 // query and for the k best candidates among the scores of its probed lists.
 //
 // Values come in fixed-width blocks with a precomputed block maximum.  Level 1 finds
-// the k-th largest block maximum M (a 32-step search on the order-preserving bits, no
-// sorting): at least k values are >= M, so every member of the top-k is >= M and lives
+// the k-th largest block maximum M (a search on the order-preserving bits, four bits per
+// round, no sorting): at least k values are >= M, so every member of the top-k is >= M and lives
 // in a block whose maximum is >= M.  Level 2 visits only those blocks, keeps the values
 // >= M (a few more than k unless scores tie massively) and sorts them with a streaming
 // top-k in LDS, so any number of blocks and any number of ties is handled exactly.
@@ -21,7 +21,7 @@ struct SelectShared {
     TopK tk;
     int qual[kChunk];   // blocks that pass level 1
     int nqual;
-    int wcount[2][kSelThreads / 64];
+    int wcount[2][kSelThreads / 64][16];   // per round parity and wavefront: counts for 15 candidate thresholds
 };
 
 // Src must provide:
@@ -47,23 +47,41 @@ __device__ inline void two_level_select(SelectShared& sh, const Src& src, int k,
     for (int i = threadIdx.x; i < min(nb, kOrdCache); i += T) ords[i] = src.block_max_ord(i);
     __syncthreads();
     auto ord_at = [&](int i) -> uint32_t { return i < kOrdCache ? ords[i] : src.block_max_ord(i); };
+    // Four bits per round: every wavefront counts, for the 15 candidate values of the next
+    // hex digit, how many of its block maxima reach the candidate; one barrier later the
+    // first 15 lanes of every wavefront add up the wavefronts' counts and the digit is the
+    // number of candidates that at least k maxima reach (the counts fall as the candidate
+    // rises).  Eight barriers instead of one per bit: the workgroup is 16 wavefronts wide
+    // and the barriers, not the counting, are what this search costs.
     uint32_t thr = 0;
     if (nb >= k) {
-        for (int bit = 31; bit >= 0; --bit) {
-            const uint32_t cand = thr | (1u << bit);
-            int c = 0;
+        for (int round = 0; round < 8; ++round) {
+            const int shift = 28 - 4 * round;
+            int cnt[15];
+#pragma unroll
+            for (int c = 0; c < 15; ++c) cnt[c] = 0;
             for (int i0 = 0; i0 < nb; i0 += T) {        // uniform trip count: ballots stay whole
-                int i = i0 + threadIdx.x;
-                bool ge = i < nb && ord_at(i) >= cand;
-                c += __popcll(__ballot(ge));
+                const int i = i0 + threadIdx.x;
+                const bool in = i < nb;
+                const uint32_t v = in ? ord_at(i) : 0u;
+#pragma unroll
+                for (int c = 0; c < 15; ++c)
+                    cnt[c] += __popcll(__ballot(in && v >= (thr | ((uint32_t)(c + 1) << shift))));
             }
-            const int slot = bit & 1;
-            if (lane == 0) sh.wcount[slot][wave] = c;
+            const int slot = round & 1;
+            int mine = 0;
+#pragma unroll
+            for (int c = 0; c < 15; ++c)
+                if (lane == c) mine = cnt[c];
+            if (lane < 15) sh.wcount[slot][wave][lane] = mine;
             __syncthreads();
             int total = 0;
+            if (lane < 15) {
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) total += sh.wcount[slot][w];
-            if (total >= k) thr = cand;
+                for (int w = 0; w < kWaves; ++w) total += sh.wcount[slot][w][lane];
+            }
+            const unsigned long long reach = __ballot(lane < 15 && total >= k);
+            thr |= (uint32_t)__popcll(reach) << shift;
         }
     }
     if (min_thr > thr) thr = min_thr;

@@ -1,6 +1,8 @@
 """GPU parity, small sizes: the HIP path (through the C ABI) against the CPU oracle,
 element by element, on seeded inputs that span several 64-vector blocks, ragged tails,
 empty lists, shared lists and the degenerate cases of the method."""
+import zlib
+
 import numpy as np
 import pytest
 
@@ -126,13 +128,17 @@ CASES = [
     ("all_lists", 5000, 64, 33, "fp16", 8, 33, 20, ()),
     ("many_blocks", 40000, 128, 5, "fp16", 6, 2, 50, ()),
     ("wide_d1024", 1500, 1024, 4, "fp32", 3, 2, 10, ()),
+    # the documented maxima: d = 4096; k = nprobe = 1024; nq = 65535
+    ("max_d4096", 600, 4096, 3, "fp16", 3, 2, 10, ()),
+    ("max_k_and_nprobe_1024", 40000, 16, 1100, "fp32", 3, 1024, 1024, (7,)),
+    ("max_nq_65535", 200, 8, 2, "fp32", 65535, 1, 1, ()),
 ]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_edge_cases_match_oracle(case):
     name, n, d, nlist, storage, nq, nprobe, k, empty = case
-    cen, vec, ids, off = _random_index(hash(name) % 1000, n, d, nlist, storage, empty)
+    cen, vec, ids, off = _random_index(zlib.crc32(name.encode()) % 1000, n, d, nlist, storage, empty)
     rng = np.random.default_rng(99)
     q = rng.standard_normal((nq, d)).astype(np.float32)
     idx = ivf.Index()
