@@ -12,11 +12,6 @@
 
 namespace ivf {
 
-__global__ void k_zero_i32(int* __restrict__ p, size_t n) {
-    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
 enum {                 // 64-bit counters accumulated by k_list_partial (zero on entry)
     kCntPairs = 0,
     kCntScoreBlocks = 1,

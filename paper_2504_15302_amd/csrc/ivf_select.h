@@ -42,7 +42,7 @@ __device__ inline void two_level_select(SelectShared& sh, const Src& src, int k,
     constexpr int kPerWave = 64 / Src::kWidth;   // blocks a wavefront visits at once
 
     // level 1: thr = k-th largest block maximum (0 if there are fewer than k blocks),
-    // found bit by bit: the largest v such that at least k block maxima are >= v.
+    // i.e. the largest v such that at least k block maxima are >= v.
     uint32_t* ords = reinterpret_cast<uint32_t*>(sh.tk.buf);
     for (int i = threadIdx.x; i < min(nb, kOrdCache); i += T) ords[i] = src.block_max_ord(i);
     __syncthreads();
