@@ -426,3 +426,35 @@ def test_error_paths_on_the_gpu(c1):
     # the index still works after the failed calls
     got = gpu_search(idx, W.queries(w), w.nprobe, w.k)
     check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, W.queries(w), w.nprobe, w.k, got, w.storage)
+
+
+def test_search_can_be_captured_in_a_hip_graph_and_replayed(c1):
+    """After one eager call with the same shapes (scratch is allocated on first use) a
+    search records only kernel launches on the caller's stream — no allocation, no host
+    synchronisation, no memset node — so a caller may capture it in a HIP graph.  Replays,
+    with eager work and synchronisations in between, are checked against eager results."""
+    import torch
+    w, h, idx = c1
+    nq = 16
+    batches = [W.queries(w, batch=30 + b, nq=nq) for b in range(4)]
+    refs = [gpu_search(idx, q, w.nprobe, w.k) for q in batches]
+    q_static = torch.from_numpy(batches[0]).cuda()
+    out_ids = torch.empty((nq, w.k), dtype=torch.int64, device="cuda")
+    out_scores = torch.empty((nq, w.k), dtype=torch.float32, device="cuda")
+    idx.search(q_static, w.nprobe, w.k, out_ids, out_scores)          # warm-up with these shapes
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    say("C1: capturing one search in a HIP graph")
+    with torch.cuda.graph(g):
+        idx.search(q_static, w.nprobe, w.k, out_ids, out_scores)
+    for rep in range(3):
+        for b, q in enumerate(batches):
+            q_static.copy_(torch.from_numpy(q).cuda())
+            out_ids.fill_(-7)
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(out_ids.cpu().numpy(), refs[b][0]), f"replay {rep}, batch {b}"
+            assert np.array_equal(out_scores.cpu().numpy(), refs[b][1])
+            eager = gpu_search(idx, batches[(b + 1) % 4], w.nprobe, w.k)   # the library's own eager work in between
+            assert np.array_equal(eager[0], refs[(b + 1) % 4][0])
+    del g
