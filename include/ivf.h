@@ -21,8 +21,9 @@
  *     its buffers and may free them when the call returns.
  *   - One search (or upload, or budget change) at a time per index: calls on the
  *     same index must not overlap.  Different indexes are independent.
- *   - Limits: d a multiple of 8 and d <= 4096; 1 <= k <= 1024; 1 <= nprobe <= 1024
- *     (nprobe above nlist is clamped to nlist); n < 2^32; nlist < 2^28.
+ *   - Limits: d a multiple of 8 (16 for IVF_INT8) and d <= 4096; 1 <= k <= 1024;
+ *     1 <= nprobe <= 1024 (nprobe above nlist is clamped to nlist); nq <= 65535 per
+ *     call; n < 2^32; nlist < 2^28; a list holds at most 65535 * 64 vectors.
  *   - Ordering rule: best first by (score descending, user id ascending, upload
  *     position ascending).  The GPU accumulates scores in fp32.
  */
@@ -261,7 +262,10 @@ int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
    2..8, "nside" 1..4 (copy streams of the staged mode), "scan_unroll" 8|16 (16-byte
    loads per lane and register buffer), "scan_waves" 1|2|4|8 (wavefronts per workgroup),
    "scan_mode" 0|1 (1 = persistent wavefronts on an atomic queue, "scan_wgs_per_cu"
-   1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always). */
+   1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always),
+   "residency_policy" 0|1 and "segment_mb" (see ivf_set_device_budget; the segment size
+   applies from the next upload), "move_chunk_kb" and "move_inflight_kb" (see
+   ivf_set_device_budget_async). */
 int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
 
 /* ---- batch-size choice for the retrieval worker (host arithmetic, no GPU) ----

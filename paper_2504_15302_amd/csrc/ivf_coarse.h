@@ -52,7 +52,8 @@ __global__ __launch_bounds__(256) void k_coarse(const float* __restrict__ Q,
                                                 int* __restrict__ zero, int nzero) {
     // The search's zero-initialised scratch (probe histogram, cursors, counters, bounds) is
     // first touched by the kernels after this one: clearing it here saves a launch.
-    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < nzero; i += gridDim.x * gridDim.y * 256)
+    for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < (size_t)nzero;
+         i += (size_t)gridDim.x * gridDim.y * 256)
         zero[i] = 0;
     __shared__ float qs[2][MT * 32 * kCoarseLd];     // query tiles of two consecutive steps
     const int lane = threadIdx.x & 63;
