@@ -112,6 +112,63 @@ def test_c4_offloaded_placement_matches_oracle_and_c3(c3):
     assert np.array_equal(got3[0], ref[0]) and np.array_equal(got3[1], ref[1])
 
 
+def test_c3_worker_serves_requests_while_the_budget_changes(c3):
+    """The pipeline's retrieval half at full size: client threads keep a worker busy while
+    its index goes from fully resident to a quarter of the lists and back (23 GB each way
+    on streams of their own); every request gets the rows of a direct search."""
+    import threading
+    import time
+    w = c3.w
+    q = W.queries(w, batch=2)                                  # 64 queries
+    ref = gpu_search(c3.index, q, w.nprobe, w.k)
+    check_large(c3, q, w.nprobe, w.k, ref, rows=[0, 63])
+    lens = np.diff(c3.off)
+    order = np.lexsort((np.arange(w.nlist), -lens))
+    keep = order[: w.nlist // 4]
+    quarter = int(((lens[keep] + 63) // 64).sum()) * 64 * w.d * 2
+    wk = ivf.Worker(c3.index, w.nprobe, w.k, 16)
+    results, stop = {}, threading.Event()
+
+    def client(c):
+        r = 0
+        while not stop.is_set():
+            i = (c * 7 + r) % 64
+            got = wk.wait(wk.submit(q[i]))
+            results[(c, r)] = (i, got)
+            r += 1
+
+    try:
+        th = [threading.Thread(target=client, args=(c,)) for c in range(4)]
+        for t in th:
+            t.start()
+        seen = []
+        for target, want in ((quarter, len(keep)), (2**62, w.nlist)):
+            say(f"C3 worker: budget change to {want} resident lists under load")
+            wk.set_device_budget(target)
+            t0 = time.time()
+            while time.time() - t0 < 120:
+                st = wk.stats()
+                seen.append(st.resident_lists)
+                if not st.budget_busy and st.resident_lists == want:
+                    break
+                time.sleep(0.02)
+            st = wk.stats()
+            assert st.budget_busy == 0 and st.budget_error == 0 and st.resident_lists == want, (st.resident_lists, want)
+        stop.set()
+        for t in th:
+            t.join(timeout=60)
+            assert not t.is_alive()
+    finally:
+        stop.set()
+        wk.stop()
+    assert len(results) > 20
+    for (c, r), (i, got) in results.items():
+        assert np.array_equal(got[0], ref[0][i]) and np.array_equal(got[1], ref[1][i]), f"client {c} request {r}"
+    assert any(len(keep) < s < w.nlist for s in seen)          # the change was seen half-way
+    say(f"C3 worker: {len(results)} requests answered during the two changes")
+    assert c3.index.info().resident_lists == w.nlist
+
+
 def test_c5_full_size_sampled_rows_match_oracle():
     w = W.CONFIGS["C5"]
     dw = DeviceWorkload(w, groups_per_chunk=32)
