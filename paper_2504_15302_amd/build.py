@@ -57,7 +57,26 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    build_demo(verbose)
     return LIB
+
+
+DEMO = os.path.join(HERE, "search_demo")
+
+
+def build_demo(verbose: bool = False) -> str:
+    """The plain-C consumer of the ABI (examples/search_demo.c), built with the host C
+    compiler against the library and the system HIP runtime."""
+    root = os.path.dirname(HERE)
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=gnu99", "-O1", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
+           "-I" + os.path.join(root, "include"), os.path.join(root, "examples", "search_demo.c"),
+           "-L" + HERE, "-livf_mi355x", "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", DEMO]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd, stderr=subprocess.DEVNULL if not verbose else None)
+    return DEMO
 
 
 if __name__ == "__main__":

@@ -62,3 +62,16 @@ def test_product_path_never_imports_the_oracle():
                 assert "oracle" not in text.replace("the oracle's tests", "").replace("CPU oracle", "") \
                     or f == "workloads.py", f"{f} mentions the oracle"
                 assert "import oracle" not in text and "from oracle" not in text
+
+
+def test_header_is_strict_c99_and_the_c_demo_builds(tmp_path):
+    """The boundary is usable from plain C: the header compiles as strict C99, and the C
+    consumer under examples/ builds against the library with the host C compiler."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "ivf.h"\nint main(void) { ivf_info i; (void)i; return IVF_OK; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I" + os.path.join(ROOT, "include"),
+                    "-c", str(src), "-o", str(tmp_path / "hdr.o")], check=True)
+    from paper_2504_15302_amd import build
+    assert os.path.exists(build.DEMO), "run python -m paper_2504_15302_amd.build"
+    assert os.path.getmtime(build.DEMO) >= os.path.getmtime(os.path.join(ROOT, "examples", "search_demo.c"))

@@ -458,3 +458,13 @@ def test_search_can_be_captured_in_a_hip_graph_and_replayed(c1):
             eager = gpu_search(idx, batches[(b + 1) % 4], w.nprobe, w.k)   # the library's own eager work in between
             assert np.array_equal(eager[0], refs[(b + 1) % 4][0])
     del g
+
+
+def test_plain_c_consumer_of_the_abi():
+    """examples/search_demo.c, built by the package's build step: upload from host arrays,
+    half of the index in pinned host memory, search, its own brute-force check."""
+    import subprocess
+    from paper_2504_15302_amd import build
+    say("running the C demo")
+    r = subprocess.run([build.DEMO], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
