@@ -468,3 +468,58 @@ def test_plain_c_consumer_of_the_abi():
     say("running the C demo")
     r = subprocess.run([build.DEMO], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+
+
+def test_two_indexes_on_two_streams_and_two_threads_do_not_interfere():
+    """Different indexes share nothing: searches on two indexes queued alternately on two
+    streams, and issued from two host threads at once, return what each index returns alone."""
+    import threading
+    import torch
+    a = _random_index(21, 9000, 64, 12, "fp16", normalise=True)
+    b = _random_index(22, 7000, 96, 9, "fp32")
+    rng = np.random.default_rng(5)
+    qa = rng.standard_normal((20, 64)).astype(np.float32)
+    qb = rng.standard_normal((33, 96)).astype(np.float32)
+    ia, ib = ivf.Index(), ivf.Index()
+    ia.upload(*a)
+    ib.upload(*b)
+    ra = gpu_search(ia, qa, 4, 10)
+    rb = gpu_search(ib, qb, 3, 17)
+    check_against_oracle(*a, qa, 4, 10, ra, "fp16", abs_floor=_floor(qa, a[1]))
+    check_against_oracle(*b, qb, 3, 17, rb, "fp32", abs_floor=_floor(qb, b[1]))
+    say("two indexes, two streams, searches queued alternately")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    da, db = torch.from_numpy(qa).cuda(), torch.from_numpy(qb).cuda()
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(20):
+        outs.append(("a", ia.search(da, 4, 10, stream=sa)))
+        outs.append(("b", ib.search(db, 3, 17, stream=sb)))
+    torch.cuda.synchronize()
+    for which, (ids, sc) in outs:
+        ref = ra if which == "a" else rb
+        assert np.array_equal(ids.cpu().numpy(), ref[0]) and np.array_equal(sc.cpu().numpy(), ref[1])
+    say("two indexes, two host threads")
+    errors = []
+
+    def worker(idx, dq, nprobe, k, ref, stream):
+        try:
+            for rep in range(50):
+                ids, sc = idx.search(dq, nprobe, k, stream=stream)
+                stream.synchronize()
+                if not (np.array_equal(ids.cpu().numpy(), ref[0]) and np.array_equal(sc.cpu().numpy(), ref[1])):
+                    errors.append(f"mismatch at repetition {rep}")
+                    return
+        except Exception as e:                      # noqa: BLE001
+            errors.append(repr(e))
+
+    th = [threading.Thread(target=worker, args=(ia, da, 4, 10, ra, sa)),
+          threading.Thread(target=worker, args=(ib, db, 3, 17, rb, sb))]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join(timeout=120)
+        assert not t.is_alive()
+    assert not errors, errors
+    ia.close()
+    ib.close()
