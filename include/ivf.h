@@ -229,10 +229,12 @@ typedef struct {
 /* Statistics of the last search; synchronises the stream it ran on. */
 int ivf_last_search_stats(ivf_index *idx, ivf_search_stats *out);
 
-/* Stage timing with HIP events on the search's own stream.  While enabled, every
-   search records events around its stages (the events of the last 64 searches are
-   kept); ivf_get_stage_ms waits for the search `back` calls ago (0 = the last one) and
-   returns its stage times in milliseconds. */
+/* Stage timing with HIP events on the search's own stream.  Level 1: every search
+   records events around all its stages; level 2: only around the scan and the streaming
+   of host lists (three event records instead of seven, which matters for searches that
+   take ~100 us; the other stages then read 0 and TOTAL covers the two); 0: off.  The
+   events of the last 64 searches are kept; ivf_get_stage_ms waits for the search `back`
+   calls ago (0 = the last one) and returns its stage times in milliseconds. */
 enum {
     IVF_STAGE_COARSE = 0,   /* centroid GEMM + tile maxima */
     IVF_STAGE_PROBE = 1,    /* top-nprobe selection */
@@ -243,7 +245,7 @@ enum {
     IVF_STAGE_TOTAL = 6,
     IVF_NUM_STAGES = 7
 };
-int ivf_set_timing(ivf_index *idx, int enable);
+int ivf_set_timing(ivf_index *idx, int level);
 int ivf_get_stage_ms(ivf_index *idx, int back, float *ms /* [IVF_NUM_STAGES] host */);
 
 /* A plain copy kernel over `bytes` bytes (multiple of 16) of DEVICE memory, enqueued on

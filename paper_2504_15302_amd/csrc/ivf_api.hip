@@ -695,10 +695,13 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     if (!x->opt_scan_prune || k > 128 || small_plan) { x->prune_blocks = 0; x->prune_j = 0; }
     else if (k <= 64) { x->prune_blocks = 1; x->prune_j = k; }
     else { x->prune_blocks = 2; x->prune_j = (k + 1) / 2; }
-    const bool tm = x->timing;
+    const int tm = x->timing;                  // 0 off, 1 every stage, 2 the scan and streaming stages only
     hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
     int evi = 0;
-    auto mark = [&]() { if (tm) (void)hipEventRecord(evs[evi], st); ++evi; };
+    auto mark = [&]() {
+        if (tm == 1 || (tm == 2 && evi >= 3 && evi <= 5)) (void)hipEventRecord(evs[evi], st);
+        ++evi;
+    };
 
     mark();   // 0
     const int nz = (int)(2 * (size_t)nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq);   // cleared by the coarse kernel
@@ -892,7 +895,8 @@ int ivf_set_timing(ivf_index* x, int enable) {
             for (int i = 0; i < kEvPerSearch; ++i) HIP_TRY(hipEventCreate(&x->ev[sl][i]));
         x->ev_created = true;
     }
-    x->timing = enable != 0;
+    if (enable < 0 || enable > 2) return fail(IVF_ERR_INVALID, "timing level must be 0, 1 or 2");
+    x->timing = enable;
     x->timed_searches = 0;
     return 0;
 }
@@ -904,6 +908,14 @@ int ivf_get_stage_ms(ivf_index* x, int back, float* ms) {
     if (back < 0 || back >= kTimingSlots || back >= x->timed_searches)
         return fail(IVF_ERR_INVALID, "no timed search %d calls back (kept: %d)", back, kTimingSlots);
     hipEvent_t* evs = x->ev[(x->timed_searches - 1 - back) % kTimingSlots];
+    for (int i = 0; i < IVF_NUM_STAGES; ++i) ms[i] = 0.f;
+    if (x->timing == 2) {                    // only the scan and streaming stages were recorded
+        HIP_TRY(hipEventSynchronize(evs[5]));
+        HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_SCAN], evs[3], evs[4]));
+        HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_STREAM], evs[4], evs[5]));
+        HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_TOTAL], evs[3], evs[5]));
+        return 0;
+    }
     HIP_TRY(hipEventSynchronize(evs[6]));
     for (int i = 0; i < 6; ++i) HIP_TRY(hipEventElapsedTime(&ms[i], evs[i], evs[i + 1]));
     HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_TOTAL], evs[0], evs[6]));

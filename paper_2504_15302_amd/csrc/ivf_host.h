@@ -202,7 +202,7 @@ struct ivf_index {
     hipStream_t last_stream = nullptr;
     bool last_offload = false;
     ivf_search_stats last_stats = {};
-    bool timing = false;
+    int timing = 0;                    // 0 off, 1 every stage, 2 scan and streaming stages only
     hipEvent_t ev[kTimingSlots][kEvPerSearch] = {};
     bool ev_created = false;
     int64_t timed_searches = 0;        // searches recorded since timing was switched on

@@ -270,8 +270,9 @@ class Index:
         _check(self._lib.ivf_last_search_stats(self._h, C.byref(out)))
         return out
 
-    def set_timing(self, enable: bool):
-        _check(self._lib.ivf_set_timing(self._h, int(enable)))
+    def set_timing(self, level):
+        """0/False off, 1/True every stage, 2 the scan and streaming stages only."""
+        _check(self._lib.ivf_set_timing(self._h, int(level)))
 
     def stage_ms(self, back: int = 0) -> dict:
         """Stage times (ms) of the timed search `back` calls ago (0 = the last one)."""

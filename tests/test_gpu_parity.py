@@ -523,3 +523,27 @@ def test_two_indexes_on_two_streams_and_two_threads_do_not_interfere():
     assert not errors, errors
     ia.close()
     ib.close()
+
+
+def test_timing_levels(c1):
+    w, h, idx = c1
+    q = W.queries(w, batch=40)
+    try:
+        idx.set_timing(1)
+        gpu_search(idx, q, w.nprobe, w.k)
+        ms = idx.stage_ms(0)
+        assert all(ms[s] > 0 for s in ("coarse", "probe", "regroup", "scan", "select"))
+        assert abs(ms["total"] - sum(ms[s] for s in ivf.STAGES[:-1])) < 0.05 * ms["total"] + 1e-3
+        idx.set_timing(2)                                   # the scan and streaming stages only
+        gpu_search(idx, q, w.nprobe, w.k)
+        ms = idx.stage_ms(0)
+        assert ms["scan"] > 0 and ms["coarse"] == 0 and ms["select"] == 0
+        assert abs(ms["total"] - ms["scan"] - ms["stream"]) < 0.05 * ms["total"] + 1e-3
+        with pytest.raises(ivf.IvfError):
+            idx.set_timing(3)
+        idx.set_timing(0)
+        gpu_search(idx, q, w.nprobe, w.k)
+        with pytest.raises(ivf.IvfError):
+            idx.stage_ms(0)                                 # nothing was timed
+    finally:
+        idx.set_timing(0)
