@@ -723,8 +723,16 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     mark();   // 1
     int* hist = s.zeroed;
     int* cursor = s.zeroed + nlist;
-    hipLaunchKernelGGL(k_probe_select, dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.S, s.tmax, nlist, ntile, nprobe,
-                       s.probes, hist);
+    // The selection kernels are chains of barriers and dependent loads: with little to select
+    // from, a workgroup of 4 wavefronts gets through them faster than one of 16.
+    const bool small_probe = x->opt_sel_threads ? x->opt_sel_threads == 256 : ntile <= 128;
+    const bool small_final = x->opt_sel_threads ? x->opt_sel_threads == 256 : block_bound(x, 1, nprobe) <= 128;
+    if (small_probe)
+        hipLaunchKernelGGL((k_probe_select<256>), dim3((unsigned)nq), dim3(256), 0, st, s.S, s.tmax, nlist, ntile, nprobe,
+                           s.probes, hist);
+    else
+        hipLaunchKernelGGL((k_probe_select<kSelThreads>), dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.S, s.tmax, nlist,
+                           ntile, nprobe, s.probes, hist);
     mark();   // 2
     if (offload) {
         HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)npairs, hipMemcpyDeviceToHost, st));
@@ -755,9 +763,14 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     }
     mark();   // 5
     ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
-    hipLaunchKernelGGL(k_final_select, dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.probes, s.pair_of_probe,
-                       s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, nprobe, k,
-                       x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
+    if (small_final)
+        hipLaunchKernelGGL((k_final_select<256>), dim3((unsigned)nq), dim3(256), 0, st, s.probes, s.pair_of_probe,
+                           s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, nprobe, k,
+                           x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
+    else
+        hipLaunchKernelGGL((k_final_select<kSelThreads>), dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.probes,
+                           s.pair_of_probe, s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos,
+                           x->d_id_sorted, nprobe, k, x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
     mark();   // 6
     HIP_TRY(hipGetLastError());
     if (offload) {
@@ -971,6 +984,7 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
     // asynchronous budget changes: size of one batch of list copies, and how much may be under way at once
+    else if (n == "sel_threads" && (value == 0 || value == 256 || value == 1024)) x->opt_sel_threads = value;   // 0: by size
     else if (n == "move_chunk_kb" && value >= 1 && value <= ((int64_t)1 << 24)) x->opt_move_chunk_kb = value;
     else if (n == "move_inflight_kb" && value >= 1 && value <= ((int64_t)1 << 26)) x->opt_move_inflight_kb = value;
     else return fail(IVF_ERR_INVALID, "unknown option or bad value: %s=%lld", name, (long long)value);

@@ -32,9 +32,8 @@ struct SelectShared {
 //   static constexpr int kWidth                    values per block (<= 64)
 // `min_thr`: a lower bound of the k-th best value's order bits that the caller already
 // knows (0 = none); blocks below it are not visited.
-template <class Src>
+template <int T, class Src>
 __device__ inline void two_level_select(SelectShared& sh, const Src& src, int k, uint32_t min_thr = 0) {
-    constexpr int T = kSelThreads;
     const int nb = src.nblocks();
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -153,7 +152,8 @@ struct CoarseSrc {
 // hist[l] (zero on entry) how many queries probe list l (low 20 bits) and, above bit 20,
 // for how many it is the best probe; of the latter only "non-zero" is used, as an
 // ordering hint for the scan, so wrap-around there is harmless.
-__global__ __launch_bounds__(kSelThreads) void k_probe_select(const float* __restrict__ S,
+template <int T>
+__global__ __launch_bounds__(T) void k_probe_select(const float* __restrict__ S,
                                                               const float* __restrict__ tmax,
                                                               int nlist, int ntile, int nprobe,
                                                               int32_t* __restrict__ probes,
@@ -161,8 +161,8 @@ __global__ __launch_bounds__(kSelThreads) void k_probe_select(const float* __res
     __shared__ SelectShared sh;
     const int q = blockIdx.x;
     CoarseSrc src{S + (size_t)q * nlist, tmax + (size_t)q * ntile, nlist, ntile};
-    two_level_select(sh, src, nprobe);
-    for (int i = threadIdx.x; i < nprobe; i += kSelThreads) {
+    two_level_select<T>(sh, src, nprobe);
+    for (int i = threadIdx.x; i < nprobe; i += T) {
         uint64_t key = sh.tk.top[i];
         uint32_t lu = ~(uint32_t)key;               // nprobe <= nlist: never an empty key,
         int32_t l = lu < (uint32_t)nlist ? (int32_t)lu : 0;   // but stay in bounds on NaN input
@@ -215,7 +215,8 @@ struct ScanSrc {
 };
 
 // One workgroup per query: the k best (score, id) over the scores the scan wrote.
-__global__ __launch_bounds__(kSelThreads) void k_final_select(
+template <int T>
+__global__ __launch_bounds__(T) void k_final_select(
     const int32_t* __restrict__ probes, const uint32_t* __restrict__ pair_of_probe,
     const uint32_t* __restrict__ pair_start, const uint32_t* __restrict__ sblk_start, ListTable lt,
     const float* __restrict__ bmax, const float* __restrict__ scores,
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(kSelThreads) void k_final_select(
     __shared__ int plen[kMaxK];
     __shared__ int64_t ppos0[kMaxK];
     const int q = blockIdx.x;
-    for (int j = threadIdx.x; j < nprobe; j += kSelThreads) {
+    for (int j = threadIdx.x; j < nprobe; j += T) {
         int l = probes[(size_t)q * nprobe + j];
         uint32_t p = pair_of_probe[(size_t)q * nprobe + j];
         int nb = lt.nblk[l];
@@ -259,8 +260,8 @@ __global__ __launch_bounds__(kSelThreads) void k_final_select(
     // the scan stored a block's scores only if its maximum reached the bound it kept for
     // the query; the final bound is at least every bound it used, so visiting only blocks
     // at or above it never reads a block that was skipped
-    two_level_select(sh, src, k, qthr ? (uint32_t)qthr[q] : 0u);
-    for (int i = threadIdx.x; i < k; i += kSelThreads) {
+    two_level_select<T>(sh, src, k, qthr ? (uint32_t)qthr[q] : 0u);
+    for (int i = threadIdx.x; i < k; i += T) {
         uint64_t key = sh.tk.top[i];
         int64_t id = -1;
         float s = -INFINITY;

@@ -358,6 +358,21 @@ def test_most_probed_lists_stay_resident_under_the_hot_policy(c1):
     idx.close()
 
 
+def test_selection_workgroup_sizes_agree(c1):
+    w, h, idx = c1
+    try:
+        for nq, nprobe, k in ((16, 8, 10), (5, 200, 1000), (40, 1, 1)):
+            q = W.queries(w, batch=50, nq=nq)
+            idx.set_option("sel_threads", 0)
+            ref = gpu_search(idx, q, nprobe, k)
+            for t in (256, 1024):
+                idx.set_option("sel_threads", t)
+                got = gpu_search(idx, q, nprobe, k)
+                assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1]) and np.array_equal(got[2], ref[2]), (t, nq, nprobe, k)
+    finally:
+        idx.set_option("sel_threads", 0)
+
+
 def test_scan_launch_options_agree(c1):
     w, h, idx = c1
     q = W.queries(w, batch=5)
