@@ -265,7 +265,8 @@ int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
    loads per lane and register buffer), "scan_waves" 1|2|4|8 (wavefronts per workgroup),
    "scan_mode" 0|1 (1 = persistent wavefronts on an atomic queue, "scan_wgs_per_cu"
    1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always),
-   "sel_threads" 0|256|1024 (workgroup size of the selection kernels; 0 = by problem size),
+   "regroup_fused" 0|1 (1 = searches with at most 1024 lists and 2048 (query, list) pairs
+   regroup in a single launch), "sel_threads" 0|256|1024 (workgroup size of the selection kernels; 0 = by problem size),
    "residency_policy" 0|1 and "segment_mb" (see ivf_set_device_budget; the segment size
    applies from the next upload), "move_chunk_kb" and "move_inflight_kb" (see
    ivf_set_device_budget_async). */

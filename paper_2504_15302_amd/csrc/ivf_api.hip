@@ -738,18 +738,23 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
         HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)npairs, hipMemcpyDeviceToHost, st));
         HIP_TRY(hipEventRecord(x->ev_probes, st));
     }
-    {
+    if (x->opt_regroup_fused && nlist <= kFusedMaxLists && npairs <= kFusedMaxPairs) {
+        // few lists and pairs: one workgroup does the whole regrouping in one launch
+        hipLaunchKernelGGL(k_regroup_small, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                           nlist, nprobe, x->block_bytes, s.probes, npairs, cursor, s.pair_start, s.sblk_start,
+                           s.item_start, s.pair_flat, s.pair_of_probe, s.items, x->d_hits, s.counters);
+    } else {
         const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
         hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
                            nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
         hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, hist, nlist, (int)wgs, s.wg_totals,
                            s.pair_start, s.sblk_start, s.item_start);
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
+                           s.pair_start, cursor, s.pair_flat);
+        hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
+                           x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
+                           s.pair_flat, s.pair_of_probe, s.items, x->d_hits);
     }
-    hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
-                       s.pair_start, cursor, s.pair_flat);
-    hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
-                       x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
-                       s.pair_flat, s.pair_of_probe, s.items, x->d_hits);
     mark();   // 3
     if (x->resident_lists > 0 || x->opt_host_direct) {
         const int mode = (int)x->opt_scan_mode;
@@ -984,6 +989,7 @@ int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     else if (n == "stage_mb" && value >= 1 && value <= 4096) x->opt_stage_mb = value;
     else if (n == "nstage" && value >= 2 && value <= kMaxStage) x->opt_nstage = value;
     // asynchronous budget changes: size of one batch of list copies, and how much may be under way at once
+    else if (n == "regroup_fused" && (value == 0 || value == 1)) x->opt_regroup_fused = value;
     else if (n == "sel_threads" && (value == 0 || value == 256 || value == 1024)) x->opt_sel_threads = value;   // 0: by size
     else if (n == "move_chunk_kb" && value >= 1 && value <= ((int64_t)1 << 24)) x->opt_move_chunk_kb = value;
     else if (n == "move_inflight_kb" && value >= 1 && value <= ((int64_t)1 << 26)) x->opt_move_inflight_kb = value;

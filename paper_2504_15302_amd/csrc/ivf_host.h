@@ -208,6 +208,6 @@ struct ivf_index {
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
     int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
-            opt_nstage = 3, opt_move_chunk_kb = 64 << 10, opt_move_inflight_kb = 4 << 20, opt_sel_threads = 0;
+            opt_nstage = 3, opt_move_chunk_kb = 64 << 10, opt_move_inflight_kb = 4 << 20, opt_sel_threads = 0, opt_regroup_fused = 1;
 };
 

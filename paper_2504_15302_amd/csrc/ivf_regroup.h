@@ -204,4 +204,140 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
     }
 }
 
+
+// The whole regrouping in one workgroup, for searches whose lists and pairs are few enough
+// that four launches cost more than the work: the same numbering as k_list_partial /
+// k_list_finish, the same segments as k_pair_fill, the same items as k_plan, with
+// workgroup barriers where the separate kernels have launch boundaries.
+constexpr int kFusedMaxLists = 1024, kFusedMaxPairs = 2048;
+__global__ __launch_bounds__(kScanThreads) void k_regroup_small(
+    const int* __restrict__ hist, const int32_t* __restrict__ nblk, const int32_t* __restrict__ len,
+    const void* const* __restrict__ list_ptr, int nlist, int nprobe, size_t block_bytes,
+    const int32_t* __restrict__ probes, int npairs, int* __restrict__ cursor,
+    uint32_t* __restrict__ pair_start, uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start,
+    uint32_t* __restrict__ pair_flat, uint32_t* __restrict__ pair_of_probe, ScanItem* __restrict__ items,
+    uint32_t* __restrict__ hits, unsigned long long* __restrict__ counters) {
+    __shared__ uint32_t wsum[kScanThreads / 64][kScanVals];
+    __shared__ uint32_t run[kScanVals];              // totals of the chunks done so far
+    __shared__ unsigned long long extra[3];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    if (t < kScanVals) run[t] = 0;
+    if (t < 3) extra[t] = 0;
+    __syncthreads();
+    // 1. exclusive prefix sums over the lists (the loop runs once for up to 1024 lists)
+    for (int c0 = 0; c0 < nlist; c0 += kScanThreads) {
+        const int l = c0 + t;
+        uint32_t v[kScanVals] = {0, 0, 0, 0};
+        unsigned long long uniq = 0, vec = 0, vres = 0;
+        bool first = false;
+        if (l < nlist) {
+            const unsigned h = (unsigned)hist[l];
+            const unsigned cnt = h & kHistCountMask;
+            if (cnt) {
+                const unsigned nb = (unsigned)nblk[l];
+                const uintptr_t lp = reinterpret_cast<uintptr_t>(list_ptr[l]);
+                const bool res = lp != 0, in_hbm = res && !(lp & 1u);
+                first = (h >> kHistTopShift) != 0;
+                v[0] = cnt;
+                v[1] = cnt * nb;
+                v[first ? 2 : 3] = res ? nb * ((cnt + kQB - 1) / kQB) : 0;
+                uniq = 1;
+                vec = (unsigned)len[l];
+                vres = in_hbm ? vec : 0;
+            }
+        }
+        uint32_t inc[kScanVals];
+#pragma unroll
+        for (int c = 0; c < kScanVals; ++c) {
+            uint32_t x = v[c];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                uint32_t y = __shfl_up(x, o);
+                if (lane >= o) x += y;
+            }
+            inc[c] = x;
+            if (lane == 63) wsum[wave][c] = x;
+        }
+        if (uniq) {
+            atomicAdd(&extra[0], uniq);
+            atomicAdd(&extra[1], vec);
+            atomicAdd(&extra[2], vres);
+        }
+        __syncthreads();
+        uint32_t base[kScanVals], total[kScanVals];
+#pragma unroll
+        for (int c = 0; c < kScanVals; ++c) { base[c] = run[c]; total[c] = 0; }
+        for (int w = 0; w < kScanThreads / 64; ++w)
+#pragma unroll
+            for (int c = 0; c < kScanVals; ++c) {
+                uint32_t x = wsum[w][c];
+                if (w < wave) base[c] += x;
+                total[c] += x;
+            }
+        if (l < nlist) {
+            pair_start[l] = base[0] + inc[0] - v[0];
+            sblk_start[l] = base[1] + inc[1] - v[1];
+            item_start[l] = first ? base[2] + inc[2] - v[2] : base[3] + inc[3] - v[3];   // within its class
+        }
+        __syncthreads();
+        if (t < kScanVals) run[t] += total[t];
+        __syncthreads();
+    }
+    if (t == 0) {
+        counters[kCntPairs] = run[0];
+        counters[kCntScoreBlocks] = run[1];
+        counters[kCntItems] = (unsigned long long)run[2] + run[3];
+        counters[kCntUnique] = extra[0];
+        counters[kCntVectors] = extra[1];
+        counters[kCntVectorsResident] = extra[2];
+    }
+    const uint32_t first_items = run[2];             // items of the other lists come after these
+    // 2. every (query, probe) pair drops into its list's segment
+    for (int f = t; f < npairs; f += kScanThreads) {
+        const int l = probes[f];
+        const int slot = atomicAdd(&cursor[l], 1);
+        pair_flat[pair_start[l] + slot] = (uint32_t)f;
+    }
+    __syncthreads();
+    // 3. per list: order the segment by query, fill the pair table, write the scan items
+    for (int l = t; l < nlist; l += kScanThreads) {
+        const unsigned h = (unsigned)hist[l];
+        const unsigned cnt = h & kHistCountMask;
+        if (!cnt) continue;
+        hits[l] += cnt;
+        const uint32_t ps = pair_start[l];
+        uint32_t* seg = pair_flat + ps;
+        for (unsigned i = 1; i < cnt; ++i) {
+            uint32_t v = seg[i];
+            int j = (int)i - 1;
+            while (j >= 0 && seg[j] > v) { seg[j + 1] = seg[j]; --j; }
+            seg[j + 1] = v;
+        }
+        for (unsigned i = 0; i < cnt; ++i) pair_of_probe[seg[i]] = ps + i;
+        const char* base = reinterpret_cast<const char*>(reinterpret_cast<uintptr_t>(list_ptr[l]) & ~(uintptr_t)1);
+        if (!base) continue;
+        const unsigned nb = (unsigned)nblk[l];
+        const unsigned ln = (unsigned)len[l];
+        const unsigned groups = (cnt + kQB - 1) / kQB;
+        const uint32_t is = item_start[l] + ((h >> kHistTopShift) != 0 ? 0u : first_items);
+        ScanItem* out = items + is;
+        for (unsigned g = 0; g < groups; ++g) {
+            const unsigned nqg = min((unsigned)kQB, cnt - g * kQB);
+            for (unsigned b = 0; b < nb; ++b) {
+                ScanItem it;
+                it.data = base + (size_t)b * block_bytes;
+                it.sblk = sblk_start[l] + g * kQB * nb + b;
+                it.nblk = nb;
+#pragma unroll
+                for (unsigned j = 0; j < kQB; ++j)
+                    it.q[j] = (uint16_t)(seg[g * kQB + min(j, nqg - 1)] / (uint32_t)nprobe);
+                it.nq = (uint16_t)nqg;
+                it.nvalid = (uint16_t)min(64u, ln - b * 64u);
+                it.pad = 0;
+                out[g * nb + b] = it;
+            }
+        }
+    }
+}
+
 }  // namespace ivf

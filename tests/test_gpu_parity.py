@@ -358,6 +358,33 @@ def test_most_probed_lists_stay_resident_under_the_hot_policy(c1):
     idx.close()
 
 
+def test_fused_and_separate_regrouping_agree(c1):
+    w, h, idx = c1
+    try:
+        for nq, nprobe, k in ((16, 8, 10), (130, 15, 7), (3, 256, 100), (250, 8, 5)):
+            q = W.queries(w, batch=51, nq=nq)
+            idx.set_option("regroup_fused", 1)
+            a = gpu_search(idx, q, nprobe, k)
+            sa = idx.last_search_stats()
+            idx.set_option("regroup_fused", 0)
+            b = gpu_search(idx, q, nprobe, k)
+            sb = idx.last_search_stats()
+            assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), (nq, nprobe, k)
+            for f in ("unique_lists", "pairs", "scanned_vectors", "scan_bytes", "scan_bytes_resident", "scan_items"):
+                assert getattr(sa, f) == getattr(sb, f), f
+        total = idx.info().index_bytes
+        idx.set_device_budget(int(total * 0.4))             # host-resident lists in the plan
+        q = W.queries(w, batch=52)
+        idx.set_option("regroup_fused", 1)
+        a = gpu_search(idx, q, w.nprobe, w.k)
+        idx.set_option("regroup_fused", 0)
+        b = gpu_search(idx, q, w.nprobe, w.k)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    finally:
+        idx.set_option("regroup_fused", 1)
+        idx.set_device_budget(2**62)
+
+
 def test_selection_workgroup_sizes_agree(c1):
     w, h, idx = c1
     try:
