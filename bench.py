@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per k_scan launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE, both
 # scaled against the library's plain copy kernel), and the summary each comes from.
 # Workloads that have not been counted report null.
-TRAFFIC_BYTES = {"C5": 1.66726e7 * 2.000 * 1024 + 5510.66 * 1024,
-                 "C5-int8": 8.38707e6 * 2.000 * 1024 + 5454.83 * 1024}
+TRAFFIC_BYTES = {"C5": 1.66729e7 * 2.000 * 1024 + 5507.56 * 1024,
+                 "C5-int8": 8.38722e6 * 2.000 * 1024 + 5468.62 * 1024}
 TRAFFIC_SOURCE = {"C5": "profiles/k_scan_C5_pmc_traffic.md",
                   "C5-int8": "profiles/k_scan_C5_int8_trace_and_traffic.md"}
 
