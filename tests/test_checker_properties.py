@@ -113,3 +113,40 @@ def test_probe_sets_may_differ_only_at_a_near_tied_boundary(seed):
     dup[0, 0] = dup[0, 1]
     with pytest.raises(AssertionError):
         CK.check_probes(dup, coarse, nprobe)
+
+
+def test_abs_floor_only_loosens_ranks_whose_score_has_cancelled():
+    """With a floor of |q||x| = 100 the ranks at 40 and 3 keep the pure 1e-5 relative bar;
+    only the ranks below 1 % of the floor (0.02, -0.01) are compared relative to the floor."""
+    ref_ids = np.array([[1, 2, 3, 4, 5]], dtype=np.int64)
+    ref_s = np.array([[40.0, 3.0, 0.02, -0.01, -7.0]])
+    ids = ref_ids[:, :4].copy()
+    exact = ref_s[:, :4].astype(np.float32)
+    CK.check_topk(ids, exact, ref_ids, ref_s, 4, 1e-5, abs_floor=100.0)
+    # a cancelled score off by 5e-4 absolute: within 1e-5 * 100, far outside 1e-5 * 0.02
+    off = exact.copy()
+    off[0, 2] += np.float32(5e-4)
+    CK.check_topk(ids, off, ref_ids, ref_s, 4, 1e-5, abs_floor=100.0)
+    with pytest.raises(AssertionError):
+        CK.check_topk(ids, off, ref_ids, ref_s, 4, 1e-5)
+    # the same absolute error on a score that has not cancelled is rejected, floor or not
+    off = exact.copy()
+    off[0, 1] += np.float32(5e-4)
+    with pytest.raises(AssertionError):
+        CK.check_topk(ids, off, ref_ids, ref_s, 4, 1e-5, abs_floor=100.0)
+    # ids: two cancelled scores 1e-4 apart may swap under the floor, 3.0 and 3.0001 may not
+    swapped = ids.copy()
+    swapped[0, 2], swapped[0, 3] = ids[0, 3], ids[0, 2]
+    near = ref_s.copy()
+    near[0, 3] = 0.02 - 1e-4
+    got = near[:, :4].astype(np.float32)
+    CK.check_topk(swapped, got, ref_ids, near, 4, 1e-5, abs_floor=100.0)
+    with pytest.raises(AssertionError):
+        CK.check_topk(swapped, got, ref_ids, near, 4, 1e-5)
+    near = ref_s.copy()
+    near[0, 1] = 3.0
+    near[0, 2] = 3.0 - 1e-4
+    swapped = ids.copy()
+    swapped[0, 1], swapped[0, 2] = ids[0, 2], ids[0, 1]
+    with pytest.raises(AssertionError):
+        CK.check_topk(swapped, near[:, :4].astype(np.float32), ref_ids, near, 4, 1e-5, abs_floor=100.0)
