@@ -274,7 +274,7 @@ int ivf_set_option(ivf_index *idx, const char *name, int64_t value);
 
 /* ---- batch-size choice for the retrieval worker (host arithmetic, no GPU) ----
  *
- * Backlog-aware batch scheduling (paper Section 4.3, Eq. 4-8).  T(B) = a * B^c models
+ * Backlog-aware batch scheduling (paper Section 4.4, Eq. 4-8).  T(B) = a * B^c models
  * the time of one ivf_search over a batch of B queries; with n requests queued, k equal
  * batches served in turn give an average latency of (k+1)/2 * T(n/k) - mean arrival time
  * (Eq. 5 for k = 1, Eq. 6); one batch is at least as good as k batches iff
@@ -296,9 +296,10 @@ int ivf_sched_avg_latency(double a, double c, int64_t n, int64_t k, double mean_
 int ivf_sched_single_batch_is_best(double c, int64_t k);
 
 /* Scores every candidate batch size for a queue of n requests and returns the best
-   (ties to the larger batch).  A candidate B < n is served as ceil(n/B) batches of B, the
-   last one partly empty: (k+1)/2 * T(B) - mean_arrival; a candidate >= n as one batch of
-   n.  best_latency may be NULL. */
+   (ties to the larger batch).  A candidate B < n is served as floor(n/B) batches of B and
+   then one batch of the r requests left over, which takes T(r); a request waits until its
+   batch is done, which gives Eq. 6 when B divides n; a candidate >= n is one batch of n
+   (Eq. 5).  best_latency may be NULL. */
 int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, int m, double mean_arrival,
                      int64_t *best_batch, double *best_latency);
 
@@ -308,7 +309,7 @@ int ivf_sched_choose(double a, double c, int64_t n, const int64_t *candidates, i
  * a retrieval queue; a worker thread forms batches on its own, runs ivf_search on a
  * stream of its own and puts each request's result in a context queue, from which the
  * consumer (the generation side) takes it.  With a backlog of n requests the worker
- * serves them in batches of the size the backlog-aware rule picks (Section 4.3;
+ * serves them in batches of the size the backlog-aware rule picks (Section 4.4;
  * candidates 1, 2, 4, ... max_batch; T(B) fitted to the worker's own batch timings; the
  * whole backlog up to max_batch until two batch sizes have been timed).
  *

@@ -2,7 +2,7 @@
 TEST INFRASTRUCTURE ONLY (tests and the benchmark's reporting); shares no code with the
 library's implementation.
 
-Follows Section 4.3, "Backlog-aware Batch Scheduling (Online)", in the paper's order and
+Follows Section 4.4, "Backlog-aware Batch Scheduling (Online)", in the paper's order and
 notation, in plain fp64 Python:
 
   T(B)  = a * B**c, a > 0, c >= 0                      processing time of a batch of B   (Eq. 4)
@@ -16,14 +16,19 @@ paper's example: 8, 16, 32, 64 for n = 64) are scored with these formulas using 
 profiled samples, and the best one is taken.
 
 Readings where the text is silent: (a, c) are fitted to profiled (B, T) samples by least
-squares on log T = log a + c log B; a candidate B that does not divide n is scored with
-k = ceil(n/B) batches of its own size B (the last one partly empty), i.e.
-L(B) = (k+1)/2 * T(B) - mean(t_i); candidates above n are scored as one batch of n; ties
-go to the larger batch (fewer launches).
+squares on log T = log a + c log B; a candidate B that does not divide n (the equations
+only cover equal batches) is scored by the same derivation as Eq. 6 applied to what the
+worker would actually serve: m = floor(n/B) batches of B, then one batch of the
+r = n - m*B requests that are left, which takes T(r).  A request's latency is the
+completion time of its batch minus its arrival, so
+L(B) = [ B * T(B) * m(m+1)/2 + r * (m * T(B) + T(r)) ] / n - mean(t_i),
+which is Eq. 6 for r = 0 and Eq. 5 for B >= n (m = 0, r = n); ties go to the larger batch
+(fewer launches).
 
-Pins (tests/test_batch_sched.py): an event-by-event simulation of serving the k batches
-one after the other reproduces Eq. 5/6; Eq. 7 agrees with comparing Eq. 5 and Eq. 6
-directly; the k = 2 threshold is the value the paper prints (tests/golden/).
+Pins (tests/test_batch_sched.py): an event-by-event simulation of serving the batches
+one after the other, request by request, reproduces Eq. 5/6 and the unequal-last-batch
+formula; Eq. 7 agrees with comparing Eq. 5 and Eq. 6 directly; the k = 2 threshold is the
+value the paper prints (tests/golden/).
 """
 from __future__ import annotations
 
@@ -64,10 +69,13 @@ def split_threshold(k: int) -> float:
 
 
 def candidate_latency(a: float, c: float, n: int, B: int, mean_arrival: float = 0.0) -> float:
-    if B >= n:
-        return batch_time(a, c, n) - mean_arrival
-    k = -(-n // B)
-    return (k + 1) / 2.0 * batch_time(a, c, B) - mean_arrival
+    m = n // B                           # full batches of B (none if B > n)
+    r = n - m * B                        # requests left for the last, smaller batch
+    tB = batch_time(a, c, B)
+    total = B * tB * m * (m + 1) / 2.0
+    if r > 0:
+        total += r * (m * tB + batch_time(a, c, r))
+    return total / n - mean_arrival
 
 
 def choose_batch_size(a: float, c: float, n: int, candidates: Iterable[int],

@@ -1,7 +1,7 @@
 // Backlog-aware batch-size choice for the retrieval worker (host arithmetic only).
 // With n requests queued, serving them as k equal batches one after the other gives an
 // average latency of (k+1)/2 * T(n/k) minus the mean arrival time, where T(B) = a * B^c
-// is the profiled time of one batch (paper Section 4.3, Eq. 4-6); one batch beats k
+// is the profiled time of one batch (paper Section 4.4, Eq. 4-6); one batch beats k
 // batches exactly when 2 k^c <= k+1 (Eq. 7).  T is fitted to measured (B, T) samples of
 // ivf_search.  Exports the ivf_sched_* part of include/ivf.h.
 #include <cmath>
@@ -54,13 +54,22 @@ int ivf_sched_choose(double a, double c, int64_t n, const int64_t* candidates, i
     for (int i = 0; i < m; ++i) {
         const int64_t B = candidates[i];
         if (B < 1) return IVF_ERR_INVALID;
-        double L;
-        if (B >= n) {
-            L = ivf_sched_batch_time(a, c, (double)n) - mean_arrival;
-        } else {
-            const int64_t k = (n + B - 1) / B;     // batches of B, the last one partly empty
-            L = 0.5 * (double)(k + 1) * ivf_sched_batch_time(a, c, (double)B) - mean_arrival;
+        // Batches served in turn: every request of a batch waits until that batch is done.
+        // Full batches of B first, then one batch with the r requests that are left (which
+        // takes T(r)); with r = 0 this is Eq. 6, with B >= n Eq. 5.
+        const int64_t full = B >= n ? 0 : n / B;
+        const int64_t r = n - full * B;
+        const double tB = ivf_sched_batch_time(a, c, (double)B);
+        double now = 0.0, waited = 0.0;             // clock; sum over requests of completion times
+        for (int64_t j = 0; j < full; ++j) {
+            now += tB;
+            waited += (double)B * now;
         }
+        if (r > 0) {
+            now += ivf_sched_batch_time(a, c, (double)r);
+            waited += (double)r * now;
+        }
+        const double L = waited / (double)n - mean_arrival;
         if (!have || L < bl || (L == bl && B > bb)) {
             have = true;
             bb = B;

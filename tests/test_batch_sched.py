@@ -1,4 +1,4 @@
-"""Backlog-aware batch-size choice (paper Section 4.3, Eq. 4-8): pins for the oracle and
+"""Backlog-aware batch-size choice (paper Section 4.4, Eq. 4-8): pins for the oracle and
 parity of the library's ivf_sched_* functions against it (host arithmetic, no GPU)."""
 import math
 import os
@@ -12,17 +12,30 @@ from paper_2504_15302_amd import ivf
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-def _simulate(a, c, n, k, arrivals):
-    """Event-by-event: all n requests are queued at time 0 of the clock that the
-    arrival times are measured on, k batches of n/k are served one after the other,
-    a request's latency is its batch's completion time minus its own arrival time."""
-    size = n // k
-    now, lat = 0.0, []
-    for j in range(k):
-        now += a * size ** c                      # this batch finishes
-        for i in range(j * size, (j + 1) * size):
+def _simulate_sizes(a, c, sizes, arrivals):
+    """Event-by-event: all requests are queued at time 0 of the clock that the arrival
+    times are measured on, batches of the given sizes are served one after the other
+    (a batch of s requests takes a * s**c), a request's latency is its batch's completion
+    time minus its own arrival time."""
+    n = sum(sizes)
+    now, lat, i = 0.0, [], 0
+    for s in sizes:
+        now += a * s ** c                         # this batch finishes
+        for _ in range(s):
             lat.append(now - arrivals[i])
+            i += 1
+    assert i == n == len(arrivals)
     return sum(lat) / n
+
+
+def _simulate(a, c, n, k, arrivals):
+    """k equal batches of n/k."""
+    return _simulate_sizes(a, c, [n // k] * k, arrivals)
+
+
+def _greedy_sizes(n, B):
+    """What a worker serves from a queue of n with batch size B: full batches, then the rest."""
+    return [B] * (n // B) + ([n % B] if n % B else []) if B < n else [n]
 
 
 # ------------------------------------------------------------------ oracle pins
@@ -80,8 +93,34 @@ def test_choice_follows_the_scaling_exponent():
         sims = {B: _simulate(1.0, c, 64, 64 // B, [0.0] * 64) for B in cands}
         best = min(sims, key=lambda B: (sims[B], -B))
         assert SO.choose_batch_size(1.0, c, 64, cands)[0] == best
-    assert SO.choose_batch_size(1.0, 0.3, 20, [8, 16, 32, 64])[0] in (32, 64)   # above n: one batch of n
-    assert SO.choose_batch_size(1.0, 0.3, 20, [32, 64])[0] == 64                # tie -> larger
+    assert SO.choose_batch_size(1.0, 0.3, 20, [32, 64])[0] == 64                # both are one batch of 20: tie -> larger
+
+
+@pytest.mark.parametrize("a,c", [(0.7, 0.0), (1.3, 0.3), (0.02, 0.585), (2.0, 1.0), (0.5, 1.7)])
+@pytest.mark.parametrize("n,B", [(20, 8), (20, 16), (20, 32), (64, 24), (7, 2), (7, 3), (100, 33), (5, 5), (6, 1), (64, 16)])
+def test_a_batch_size_that_does_not_divide_the_queue_equals_the_simulation(a, c, n, B):
+    """Full batches of B, then the r requests that are left in a batch that takes T(r)."""
+    rng = np.random.default_rng(n * 131 + B)
+    arrivals = (-rng.random(n) * 3.0).tolist()
+    want = _simulate_sizes(a, c, _greedy_sizes(n, B), arrivals)
+    got = SO.candidate_latency(a, c, n, B, sum(arrivals) / n)
+    assert abs(got - want) <= 1e-12 * max(1.0, abs(want))
+    if n % B == 0 and B < n:                      # reduces to Eq. 6
+        assert abs(got - SO.avg_latency_equal_batches(a, c, n, n // B, sum(arrivals) / n)) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_choice_with_a_queue_no_candidate_divides_is_the_simulated_best():
+    for c in (0.1, 0.5, 0.7, 1.0, 1.4):
+        for n in (20, 37, 50, 63):
+            cands = [8, 16, 32, 64]
+            sims = {B: _simulate_sizes(1.0, c, _greedy_sizes(n, B), [0.0] * n) for B in cands}
+            best_B = min(sims, key=lambda B: (sims[B], -B))
+            got_B, got_L = SO.choose_batch_size(1.0, c, n, cands)
+            assert abs(got_L - sims[best_B]) <= 1e-12 * sims[best_B]
+            # ties (32 and 64 both serve n <= 32 as one batch) go to the larger candidate
+            assert got_B == max(B for B in cands if abs(sims[B] - sims[best_B]) <= 1e-15 * sims[best_B])
+    assert SO.choose_batch_size(1.0, 0.3, 20, [8, 16, 32, 64])[0] == 64           # flat time: one batch of 20
+    assert SO.choose_batch_size(1.0, 1.0, 20, [8, 16, 32, 64])[0] == 8            # linear time: 8 + 8 + 4
 
 
 # ------------------------------------------------------------------ library vs oracle

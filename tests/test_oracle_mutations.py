@@ -134,7 +134,10 @@ SCHED_MUTATIONS = [
     ("Eq. 7 with k instead of k+1", "return 2.0 * k ** c <= k + 1", "return 2.0 * k ** c <= k"),
     ("threshold with the wrong logarithm", "return math.log((k + 1) / 2.0) / math.log(k)", "return math.log((k + 1) / 2.0) / math.log(2 * k)"),
     ("fit returns the slope of T on B", "ys = [math.log(t) for t in Ts]", "ys = [t for t in Ts]"),
-    ("candidates above n are not capped", "if B >= n:\n        return batch_time(a, c, n) - mean_arrival", "if False:\n        return batch_time(a, c, n) - mean_arrival"),
+    ("the last, smaller batch is charged T(B)", "total += r * (m * tB + batch_time(a, c, r))", "total += r * (m * tB + tB)"),
+    ("the last batch does not wait for the full ones", "total += r * (m * tB + batch_time(a, c, r))", "total += r * batch_time(a, c, r)"),
+    ("full batches counted m(m-1)/2 times", "total = B * tB * m * (m + 1) / 2.0", "total = B * tB * m * (m - 1) / 2.0"),
+    ("average over the full batches only", "return total / n - mean_arrival", "return total / max(1, m * B) - mean_arrival"),
     ("ties go to the smaller batch", "(L == best_L and B > best_B)", "(L == best_L and B < best_B)"),
     ("the worst candidate wins", "L < best_L or", "L > best_L or"),
 ]
@@ -148,7 +151,10 @@ def _sched_pins():
     calls += [lambda k=k: PB.test_equation_7_is_the_comparison_of_equations_5_and_6(k) for k in (2, 4, 16)]
     calls += [PB.test_k2_threshold_is_the_value_the_paper_prints,
               PB.test_fit_recovers_an_exact_power_law_and_matches_a_library_polyfit,
-              PB.test_choice_follows_the_scaling_exponent]
+              PB.test_choice_follows_the_scaling_exponent,
+              PB.test_choice_with_a_queue_no_candidate_divides_is_the_simulated_best]
+    for n, B in [(20, 8), (20, 32), (7, 3), (64, 16)]:
+        calls.append(lambda n=n, B=B: PB.test_a_batch_size_that_does_not_divide_the_queue_equals_the_simulation(1.3, 0.3, n, B))
     return calls
 
 
