@@ -62,6 +62,7 @@ def check_against_oracle(cen, vec, ids, off, q, nprobe, k, got, storage: str, ex
     o_ids, o_scores = O.scan_select(vec, ids, off, q, use, k + extra_rows)
     res = CK.check_topk(g_ids, g_scores, o_ids, o_scores, k, CK.SCORE_REL[storage], abs_floor=abs_floor)
     CK.check_ids_in_probed_lists(g_ids, use, ids, off)
+    res["probe_sets_equal"] = bool(same)     # False: the oracle re-scanned the GPU's near-tied probe set
     return res
 
 
@@ -111,10 +112,12 @@ class DeviceWorkload:
         return vec, ids, coff, cmap
 
 
-def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, rows=None, extra_rows: int = 8):
+def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, rows=None, extra_rows: int = 8,
+                row_chunk: int = 32):
     """Parity at full size: coarse scores and probe sets for every query (centroids are
-    small), scan + selection for the query rows in `rows` (all if None), with only the
-    probed lists brought to the host."""
+    small), scan + selection for the query rows in `rows` (all if None), `row_chunk` rows
+    at a time with only their probed lists brought to the host (regenerated from the
+    seeded recipe), so that the host never holds more than a chunk's lists."""
     g_ids, g_scores, g_probes, g_coarse = got
     w = dw.w
     nprobe = min(nprobe, w.nlist)
@@ -125,12 +128,20 @@ def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, row
     assert (err <= 1e-5 * np.maximum(scale, 1e-30)).all(), "coarse scores off"
     same = CK.check_probes(g_probes, o_coarse, nprobe)
     use = O.probe_select(o_coarse, nprobe) if same else g_probes
-    rows = list(range(q.shape[0])) if rows is None else list(rows)
-    vec, ids, coff, cmap = dw.host_lists(use[rows].ravel())
-    cprobes = np.vectorize(cmap.get)(use[rows]).astype(np.int32)
-    o_ids, o_scores = O.scan_select(vec, ids, coff, q[rows], cprobes, k + extra_rows)
-    res = CK.check_topk(g_ids[rows], g_scores[rows], o_ids, o_scores, k, CK.SCORE_REL[w.storage])
-    CK.check_ids_in_probed_lists(g_ids[rows], cprobes, ids, coff)
+    all_rows = list(range(q.shape[0])) if rows is None else list(rows)
+    res = {"queries": 0, "tie_runs_reordered": 0, "probe_sets_equal": bool(same)}
+    for c0 in range(0, len(all_rows), row_chunk):
+        rows = all_rows[c0:c0 + row_chunk]
+        vec, ids, coff, cmap = dw.host_lists(use[rows].ravel())
+        cprobes = np.vectorize(cmap.get)(use[rows]).astype(np.int32)
+        o_ids, o_scores = O.scan_select(vec, ids, coff, q[rows], cprobes, k + extra_rows)
+        r = CK.check_topk(g_ids[rows], g_scores[rows], o_ids, o_scores, k, CK.SCORE_REL[w.storage])
+        CK.check_ids_in_probed_lists(g_ids[rows], cprobes, ids, coff)
+        res["queries"] += r["queries"]
+        res["tie_runs_reordered"] += r["tie_runs_reordered"]
+        del vec, ids
+        if len(all_rows) > row_chunk:
+            say(f"{w.name}: rows {rows[0]}..{rows[-1]} match the oracle")
     # properties that hold for every row at any size
     assert np.all(g_scores[:, :-1] >= g_scores[:, 1:])
     for r in range(q.shape[0]):
