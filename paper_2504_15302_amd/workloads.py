@@ -32,6 +32,7 @@ host).  They follow the same recipe but different random streams.
 """
 from __future__ import annotations
 
+import functools
 from dataclasses import dataclass, replace
 from typing import Iterator, Optional, Tuple
 
@@ -40,7 +41,7 @@ import numpy as np
 GROUP = 64  # lists per generation group
 _MASTER = 250415302
 
-_STREAM_MEANS, _STREAM_SIZES, _STREAM_NOISE, _STREAM_QUERY, _STREAM_IDS = range(5)
+_STREAM_MEANS, _STREAM_SIZES, _STREAM_NOISE, _STREAM_QUERY, _STREAM_IDS, _STREAM_CODEBOOK = range(6)
 
 
 @dataclass(frozen=True)
@@ -50,20 +51,23 @@ class Workload:
     d: int
     nlist: int
     sigma: float
-    storage: str          # "fp32" | "fp16" | "int8" (records of d codes + fp32 scale)
+    storage: str          # "fp32" | "fp16" | "int8" (records of d codes + fp32 scale) | "pq8" (pq_m codes)
     nq: int
     nprobe: int
     k: int
     seed: int
     resident_list_frac: Optional[float] = None  # None = everything HBM-resident
+    pq_m: int = 0         # "pq8": number of subspaces (one byte of code each)
 
     @property
     def elem_bytes(self) -> int:
-        return {"fp32": 4, "fp16": 2, "int8": 1}[self.storage]
+        return {"fp32": 4, "fp16": 2, "int8": 1, "pq8": 1}[self.storage]
 
     @property
     def row_bytes(self) -> int:
         """Bytes of one stored vector as uploaded."""
+        if self.storage == "pq8":
+            return self.pq_m
         return self.d * self.elem_bytes + (4 if self.storage == "int8" else 0)
 
     @property
@@ -84,6 +88,13 @@ CONFIGS = {
 # codes with one scale per vector (quantize_int8_*).  Same seeds, same queries.
 for _name in ("C1", "C3", "C5"):
     CONFIGS[_name + "-int8"] = replace(CONFIGS[_name], name=_name + "-int8", storage="int8")
+
+
+# ... and as product-quantisation codes: 8 dimensions per one-byte code (96 bytes per vector
+# at d = 768, a sixteenth of the fp16 index), codebooks drawn from the same mixture.
+for _name in ("C1", "C3", "C5"):
+    CONFIGS[_name + "-pq"] = replace(CONFIGS[_name], name=_name + "-pq", storage="pq8",
+                                     pq_m=CONFIGS[_name].d // 8)
 
 
 def scaled(w: Workload, **kw) -> Workload:
@@ -116,15 +127,22 @@ def list_offsets(w: Workload) -> np.ndarray:
     return off
 
 
-def queries(w: Workload, batch: int = 0, nq: Optional[int] = None) -> np.ndarray:
+def queries(w: Workload, batch: int = 0, nq: Optional[int] = None, components: Optional[int] = None) -> np.ndarray:
     """[nq, d] float32 unit query embeddings of batch number `batch`.  The first
-    rows of a batch do not depend on nq, so C4's 8 queries are C3's first 8."""
+    rows of a batch do not depend on nq, so C4's 8 queries are C3's first 8.
+    With `components` = m the batch is skewed: its queries come from only m mixture
+    components (drawn per batch), so about nq/m queries probe the same lists."""
     nq = w.nq if nq is None else nq
     cen = centroids(w)
     out = np.empty((nq, w.d), dtype=np.float32)
+    hot = None
+    if components is not None:
+        hot = np.random.default_rng([w.seed, _STREAM_QUERY, batch, 1 << 20]).choice(w.nlist, size=components, replace=False)
     for i in range(nq):
         rng = np.random.default_rng([w.seed, _STREAM_QUERY, batch, i])
         comp = int(rng.integers(0, w.nlist))
+        if hot is not None:
+            comp = int(hot[comp % components])
         g = rng.standard_normal(w.d).astype(np.float32)
         x = cen[comp] + np.float32(w.sigma) * g
         out[i] = x / np.linalg.norm(x)
@@ -160,6 +178,53 @@ def quantize_int8_device(x):
     return out
 
 
+@functools.lru_cache(maxsize=4)
+def pq_codebooks(w: Workload) -> np.ndarray:
+    """[pq_m, 256, d/pq_m] float32 codebooks for "pq8" storage (data preparation: the
+    library takes them as given, like the centroids).  Not trained: codeword c of every
+    subspace is the matching slice of the c-th of 256 vectors drawn from the mixture with
+    the recipe of the stored vectors (a k-means initialisation), which is all the search
+    path needs — it is exact over whatever the codes stand for."""
+    assert w.storage == "pq8" and w.pq_m > 0 and w.d % w.pq_m == 0
+    cen = centroids(w)
+    rng = _rng(w, _STREAM_CODEBOOK)
+    comp = rng.integers(0, w.nlist, size=256)
+    x = cen[comp] + np.float32(w.sigma) * rng.standard_normal((256, w.d), dtype=np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    dsub = w.d // w.pq_m
+    return np.ascontiguousarray(x.astype(np.float32).reshape(256, w.pq_m, dsub).transpose(1, 0, 2))
+
+
+def pq_encode_host(x: np.ndarray, codebooks: np.ndarray) -> np.ndarray:
+    """Data preparation for "pq8" storage: [rows, d] float32 -> [rows, M] uint8, code m =
+    the codeword of subspace m nearest to the vector's slice in Euclidean distance
+    (ties to the smaller code), computed in float32 as argmin of |c|^2 - 2 <x_m, c>."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    M, _, dsub = codebooks.shape
+    out = np.empty((x.shape[0], M), dtype=np.uint8)
+    for m in range(M):
+        cb = codebooks[m]
+        cost = (cb * cb).sum(axis=1)[None, :] - np.float32(2.0) * (x[:, m * dsub:(m + 1) * dsub] @ cb.T)
+        out[:, m] = np.argmin(cost, axis=1).astype(np.uint8)
+    return out
+
+
+def pq_encode_device(x, codebooks_dev, rows_per_step: int = 32768):
+    """The same on a torch device tensor [rows, d] float32 -> [rows, M] uint8 (batched over
+    the subspaces, a slab of rows at a time so that the cost matrix stays small)."""
+    import torch
+    M, _, dsub = codebooks_dev.shape
+    rows = x.shape[0]
+    out = torch.empty((rows, M), dtype=torch.uint8, device=x.device)
+    c2 = (codebooks_dev * codebooks_dev).sum(dim=2)                       # [M, 256]
+    cbt = codebooks_dev.transpose(1, 2).contiguous()                      # [M, dsub, 256]
+    for r0 in range(0, rows, rows_per_step):
+        xs = x[r0:r0 + rows_per_step].reshape(-1, M, dsub).transpose(0, 1)     # [M, rows, dsub]
+        cost = c2[:, None, :] - 2.0 * torch.bmm(xs, cbt)                       # [M, rows, 256]
+        out[r0:r0 + rows_per_step] = torch.argmin(cost, dim=2).transpose(0, 1).to(torch.uint8)
+    return out
+
+
 def split_int8_records(rec: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """[rows, d+4] uint8 records -> (codes [rows, d] int8, scales [rows] float32)."""
     rec = np.ascontiguousarray(rec, dtype=np.uint8)
@@ -184,6 +249,8 @@ def group_vectors_host(w: Workload, cen: np.ndarray, off: np.ndarray, group: int
     x /= np.linalg.norm(x, axis=1, keepdims=True)
     if w.storage == "int8":
         return quantize_int8_host(x)
+    if w.storage == "pq8":
+        return pq_encode_host(x, pq_codebooks(w))
     return x.astype(np.float16 if w.storage == "fp16" else np.float32)
 
 
@@ -194,6 +261,7 @@ def group_vectors_device(w: Workload, cen_dev, off: np.ndarray, group_begin: int
     import torch
     parts = []
     gen = torch.Generator(device=device)
+    cb_dev = torch.from_numpy(pq_codebooks(w)).to(device) if w.storage == "pq8" else None
     for group in range(group_begin, group_end):
         l0, l1, r0, r1 = _group_rows(w, off, group)
         rows = r1 - r0
@@ -204,6 +272,7 @@ def group_vectors_device(w: Workload, cen_dev, off: np.ndarray, group_begin: int
         g.mul_(w.sigma).add_(cen_dev[label])
         g.div_(torch.linalg.vector_norm(g, dim=1, keepdim=True))
         parts.append(quantize_int8_device(g) if w.storage == "int8" else
+                     pq_encode_device(g, cb_dev) if w.storage == "pq8" else
                      g.to(torch.float16) if w.storage == "fp16" else g)
     return torch.cat(parts, dim=0) if len(parts) != 1 else parts[0]
 

@@ -184,3 +184,60 @@ def test_a_planted_mistake_in_the_scheduling_oracle_is_caught(name, old, new):
     finally:
         PB.SO = good
     assert caught >= 1, f"no pin notices: {name}"
+
+
+# ------------------------------------------------------------ the product-quantisation oracle
+import tests.test_oracle_pq as PP
+from oracle import pq_oracle as PQO
+
+PQ_SRC = open(PQO.__file__).read().replace("from . import ivf_oracle as O", "from oracle import ivf_oracle as O")
+
+PQ_MUTATIONS = [
+    ("subspace slices overlap", "qm = q[m * dsub:(m + 1) * dsub].astype(np.float64)", "qm = q[m:m + dsub].astype(np.float64)"),
+    ("codebook of the wrong subspace", "T[m] += qm[t] * codebooks[m][:, t].astype(np.float64)", "T[m] += qm[t] * codebooks[0][:, t].astype(np.float64)"),
+    ("a dimension of every subspace dropped", "for t in range(dsub):", "for t in range(dsub - 1):"),
+    ("last subspace left out of the score", "for m in range(T.shape[0]):", "for m in range(T.shape[0] - 1):"),
+    ("codes read transposed", "s += T[m][codes[:, m]]", "s += T[m][codes[:, T.shape[0] - 1 - m]]"),
+    ("table entries subtracted", "s += T[m][codes[:, m]]", "s -= T[m][codes[:, m]]"),
+    ("worst candidates first", "order = np.lexsort((pos, ids[pos], -s))[:kout]", "order = np.lexsort((pos, ids[pos], s))[:kout]"),
+    ("ties to the larger id", "order = np.lexsort((pos, ids[pos], -s))[:kout]", "order = np.lexsort((pos, -ids[pos], -s))[:kout]"),
+    ("decode copies the wrong codeword", "out[:, m * dsub:(m + 1) * dsub] = codebooks[m][codes[:, m]]", "out[:, m * dsub:(m + 1) * dsub] = codebooks[m][255 - codes[:, m]]"),
+    ("one probed list skipped", "for l in probes[r]]", "for l in probes[r][1:]]"),
+]
+
+
+def _pq_pins():
+    calls = [PP.test_hand_worked_case,
+             PP.test_codes_that_reproduce_their_vectors_reduce_to_the_flat_search_on_the_originals]
+    calls += [lambda s=s: PP.test_table_scores_equal_a_library_matmul_against_the_decoded_vectors(s) for s in (0, 1)]
+    calls += [lambda k=k: PP.test_all_lists_probed_equals_exhaustive_search_over_the_decoded_vectors(0, k) for k in (1, 10, 600)]
+    calls += [lambda: PP.test_matches_the_flat_oracle_on_the_decoded_vectors_for_any_nprobe(0)]
+    return calls
+
+
+def _pq_failures():
+    n = 0
+    for call in _pq_pins():
+        try:
+            call()
+        except AssertionError:
+            n += 1
+    return n
+
+
+def test_unmutated_pq_oracle_passes_its_pins():
+    assert _pq_failures() == 0
+
+
+@pytest.mark.parametrize("name,old,new", PQ_MUTATIONS, ids=[m[0] for m in PQ_MUTATIONS])
+def test_a_planted_mistake_in_the_pq_oracle_is_caught(name, old, new):
+    assert PQ_SRC.count(old) >= 1, f"mutation '{name}' no longer matches the oracle source"
+    mutant = types.ModuleType("mutant_pq_oracle")
+    exec(compile(PQ_SRC.replace(old, new), "mutant_pq_oracle.py", "exec"), mutant.__dict__)
+    good = PP.PQ
+    try:
+        PP.PQ = mutant
+        caught = _pq_failures()
+    finally:
+        PP.PQ = good
+    assert caught >= 1, f"no pin notices: {name}"
