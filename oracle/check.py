@@ -12,7 +12,7 @@ from typing import List, Optional
 import numpy as np
 
 TIE_REL = 1e-5
-SCORE_REL = {"fp32": 1e-5, "fp16": 2e-3, "int8": 1e-5}   # int8: exact codes, fp32 accumulate
+SCORE_REL = {"fp32": 1e-5, "fp16": 2e-3, "int8": 1e-5, "pq8": 1e-5}   # int8, pq8: exact codes, fp32 accumulate
 # A score counts as "cancelled" when it is below this fraction of |q|*|x|: its terms have
 # eaten at least two decimal digits of each other.  Only such scores may use `abs_floor`.
 CANCEL_FRAC = 1e-2

@@ -79,6 +79,7 @@ class DeviceWorkload:
     def __init__(self, w: W.Workload, groups_per_chunk: int = 16):
         from paper_2504_15302_amd.loader import load_workload
         lw = load_workload(w, groups_per_chunk, log=say)
+        self.lw = lw
         self.w = w
         self.cen, self.off = lw.centroids, lw.offsets
         self.cen_dev, self.ids_dev, self.index = lw.centroids_dev, lw.ids_dev, lw.index
@@ -86,30 +87,9 @@ class DeviceWorkload:
 
     def host_lists(self, lists):
         """Row-major host copy of the given lists, regenerated from the seeded recipe
-        (not read back from the library): a compact sub-index (vectors, ids, offsets,
-        global->compact map)."""
-        lists = sorted(set(int(l) for l in lists))
-        by_group = {}
-        for l in lists:
-            by_group.setdefault(l // W.GROUP, []).append(l)
-        parts, idp, lens = {}, {}, {}
-        for g, ls in by_group.items():
-            gv = W.group_vectors_device(self.w, self.cen_dev, self.off, g, g + 1)
-            base = int(self.off[g * W.GROUP])
-            for l in ls:
-                a, b = int(self.off[l]) - base, int(self.off[l + 1]) - base
-                parts[l] = gv[a:b].cpu().numpy()
-                idp[l] = self.ids_dev[int(self.off[l]):int(self.off[l + 1])].cpu().numpy()
-                lens[l] = b - a
-            del gv
-        coff = np.zeros(len(lists) + 1, dtype=np.int64)
-        np.cumsum([lens[l] for l in lists], out=coff[1:])
-        vec = np.concatenate([parts[l] for l in lists], axis=0) if lists else \
-            np.empty((0, self.w.row_bytes // self.w.elem_bytes if self.w.storage != "int8" else self.w.d + 4),
-                     dtype={"fp32": np.float32, "fp16": np.float16, "int8": np.uint8}[self.w.storage])
-        ids = np.concatenate([idp[l] for l in lists]) if lists else np.empty(0, np.int64)
-        cmap = {l: i for i, l in enumerate(lists)}
-        return vec, ids, coff, cmap
+        (not read back from the library)."""
+        from paper_2504_15302_amd.loader import host_lists
+        return host_lists(self.lw, lists)
 
 
 def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, rows=None, extra_rows: int = 8,
@@ -134,6 +114,9 @@ def check_large(dw: DeviceWorkload, q: np.ndarray, nprobe: int, k: int, got, row
         rows = all_rows[c0:c0 + row_chunk]
         vec, ids, coff, cmap = dw.host_lists(use[rows].ravel())
         cprobes = np.vectorize(cmap.get)(use[rows]).astype(np.int32)
+        if w.storage == "pq8":       # the codes stand for decoded float32 vectors: the flat oracle over those
+            from oracle import pq_oracle as PQ
+            vec = PQ.decode(vec, W.pq_codebooks(w))
         o_ids, o_scores = O.scan_select(vec, ids, coff, q[rows], cprobes, k + extra_rows)
         r = CK.check_topk(g_ids[rows], g_scores[rows], o_ids, o_scores, k, CK.SCORE_REL[w.storage])
         CK.check_ids_in_probed_lists(g_ids[rows], cprobes, ids, coff)
