@@ -5,10 +5,18 @@ A step is one pass of the whole hot path (coarse quantisation, probe selection,
 regrouping, list scan, k-selection) over one batch of synthetic queries, with the
 index and the queries already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--others C1,C2,C3,C4]
 
 The default workload is C5 (100 M x 768 fp16, nq 128, nprobe 128, k 100): the
-configuration the benchmark's target is quoted on, and it fits one GPU.
+configuration the benchmark's target is quoted on, and it fits one GPU.  The other
+configurations are measured after it in the same run and reported under
+`other_configs` of the same line.
+
+Timing definitions (all reported; `value` is the first):
+  queued        K searches issued back to back with ivf_search_queued (stages of
+                neighbouring searches overlap), one synchronisation at the end, mean
+  plain_queued  the same with ivf_search (each search a chain on one stream), mean
+  single        K searches, each followed by a stream synchronisation, median
 """
 import argparse
 import json
@@ -34,16 +42,16 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
+def cpu_baseline(lw, q, got_ids, got_scores, nprobe, k, target_seconds):
     """The CPU oracle, as it stands, timed on the host cores for a bounded sample of
-    the same batch; the sampled rows are also compared with the GPU's."""
+    the same batch; the sampled rows are also compared with the GPU's.  The oracle reads
+    lists regenerated from the seeded recipe, never the library's own storage."""
     import numpy as np
     from oracle import check as CK
     from oracle import ivf_oracle as O
-    from paper_2504_15302_amd import ivf
+    from paper_2504_15302_amd.loader import host_lists
 
     w = lw.w
-    dt = {"fp32": ivf.IVF_FP32, "fp16": ivf.IVF_FP16, "int8": ivf.IVF_INT8}[w.storage]
 
     def run(rows):
         qs = q[rows]
@@ -51,17 +59,7 @@ def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
         cs = O.coarse(qs, lw.centroids)
         pr = O.probe_select(cs, nprobe)
         t_coarse = time.perf_counter() - t0
-        lists = sorted(set(int(x) for x in pr.ravel()))
-        parts, idp = [], []
-        off = np.zeros(len(lists) + 1, dtype=np.int64)
-        for i, l in enumerate(lists):           # data comes from the library's own storage
-            v, ii = idx.read_list(l, w.d, dt)
-            parts.append(v)
-            idp.append(ii)
-            off[i + 1] = off[i] + len(ii)
-        vec = np.concatenate(parts, axis=0)
-        ids = np.concatenate(idp)
-        cmap = {l: i for i, l in enumerate(lists)}
+        vec, ids, off, cmap = host_lists(lw, pr.ravel())
         cpr = np.vectorize(cmap.get)(pr).astype(np.int32)
         t1 = time.perf_counter()
         oi, os_ = O.scan_select(vec, ids, off, qs, cpr, k + 8)
@@ -80,7 +78,8 @@ def cpu_baseline(lw, idx, q, got_ids, got_scores, nprobe, k, target_seconds):
     return {"value": n / t, "unit": "queries/s", "cores": O.threads(), "kind": "oracle",
             "sample": f"first {n} of the {q.shape[0]} queries of batch 0 (fp64 coarse + probe "
                       f"selection + exact scan of their probed lists + sort), search only, "
-                      f"lists already in host RAM; {t:.1f} s; rows checked against the GPU result",
+                      f"lists regenerated from the seed into host RAM beforehand; {t:.1f} s; rows checked "
+                      f"against the GPU result",
             "seconds": t}
 
 
@@ -139,12 +138,174 @@ def budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log):
     return out
 
 
+def workload_label(w):
+    return (f"{w.name}: IVF-Flat inner product, N={w.n}, d={w.d}, {w.storage} storage, nlist={w.nlist}, "
+            f"nq={w.nq}, nprobe={w.nprobe}, k={w.k}"
+            + (f", {w.resident_list_frac:.0%} of lists HBM-resident" if w.resident_list_frac else ""))
+
+
+def pinned_h2d_rate():
+    """The box's own pinned host-to-device copy rate (1 GiB copies): the denominator for
+    lists that cross PCIe."""
+    import torch
+    hsrc = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+    ddst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    ddst.copy_(hsrc, non_blocking=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(4):
+        ddst.copy_(hsrc, non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    return 4 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None):
+    """All timing definitions for one workload on an index that is already placed.
+    Returns (report dict, query batches on host and device, first batch's results, output buffers)."""
+    import numpy as np
+    import torch
+    from paper_2504_15302_amd import workloads as W
+
+    q_host = [W.queries(w, batch=b, components=components) for b in range(nb)]
+    q_dev = [torch.from_numpy(q).cuda() for q in q_host]
+    out_ids = torch.empty((w.nq, w.k), dtype=torch.int64, device="cuda")
+    out_scores = torch.empty((w.nq, w.k), dtype=torch.float32, device="cuda")
+    # every search of the measurement goes to one stream of the benchmark's own (the legacy
+    # default stream synchronises implicitly with other streams)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    idx.set_timing(2)
+    stats, first = [], None
+    for b in range(nb):                      # also the first warm-up of every batch
+        idx.search(q_dev[b], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+        torch.cuda.synchronize()
+        stats.append(idx.last_search_stats())
+        if b == 0:
+            first = (out_ids.cpu().numpy().copy(), out_scores.cpu().numpy().copy())
+    for i in range(max(warmup, 3)):          # every scratch set of the queued path gets its size here
+        idx.search_queued(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+    torch.cuda.synchronize()
+
+    # timed region (the headline): K queued searches; only the scan carries HIP events
+    idx.set_timing(2)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        idx.search_queued(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+    torch.cuda.synchronize()
+    ms_queued = (time.perf_counter() - t0) / steps * 1e3
+    last = (out_ids.cpu().numpy(), out_scores.cpu().numpy())
+    kept = min(steps, 64)
+    scan_ms, scan_bytes, stream_ms = [], [], []
+    for back in range(kept):
+        step = steps - 1 - back
+        ms = idx.stage_ms(back)
+        st = stats[step % nb]
+        scan_ms.append(ms["scan"])
+        stream_ms.append(ms["stream"])
+        # with host lists read in place, the one scan launch covers both HBM and PCIe bytes
+        scan_bytes.append(st.scan_bytes if direct else st.scan_bytes_resident)
+    rows_ok = bool(np.array_equal(last[0], first[0]) and np.array_equal(last[1], first[1])) if (steps - 1) % nb == 0 else None
+
+    # the same K steps with plain ivf_search, queued back to back
+    for i in range(2):
+        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+    torch.cuda.synchronize()
+    ms_plain = (time.perf_counter() - t0) / steps * 1e3
+    plain_scan_ms = float(np.mean([idx.stage_ms(b)["scan"] for b in range(kept)]))
+
+    # one search at a time, each synchronised: median
+    singles = []
+    for i in range(steps):
+        t0 = time.perf_counter()
+        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+        torch.cuda.synchronize()
+        singles.append((time.perf_counter() - t0) * 1e3)
+    ms_single = float(np.median(singles))
+
+    avg_scan_ms = float(np.mean(scan_ms))
+    avg_scan_bytes = float(np.mean(scan_bytes))
+    achieved = avg_scan_bytes / (avg_scan_ms * 1e-3) / 1e9 if avg_scan_ms > 0 else 0.0
+    rep = {
+        "queries_per_s": w.nq / (ms_queued * 1e-3),
+        "ms_per_step": ms_queued,
+        "timing": {"queued_ms": ms_queued, "plain_queued_ms": ms_plain, "single_sync_median_ms": ms_single,
+                   "queries_per_s_plain_queued": w.nq / (ms_plain * 1e-3),
+                   "queries_per_s_single": w.nq / (ms_single * 1e-3),
+                   "rows_of_last_step_equal_first_search": rows_ok},
+        "scan": {"GBps": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS, "ms_per_launch": avg_scan_ms,
+                 "bytes_per_launch": avg_scan_bytes, "launches_timed": kept,
+                 "ms_per_launch_plain_search": plain_scan_ms,
+                 "GBps_plain_search": avg_scan_bytes / (plain_scan_ms * 1e-3) / 1e9 if plain_scan_ms > 0 else None},
+        "unique_lists_per_batch": int(stats[0].unique_lists),
+        "pairs_per_batch": int(stats[0].pairs),
+        "queries_per_probed_list": stats[0].pairs / max(1, stats[0].unique_lists),
+        # what the scan kernel asks memory for: one read of a block per group of up to four
+        # queries that probe its list (equal to the algorithmic bytes when no list has more)
+        "scan_requested_bytes_per_batch": int(stats[0].scan_items) * 64 * w.row_bytes,
+        "scan_bytes_per_batch": int(stats[0].scan_bytes),
+        "scan_bytes_streamed_per_batch": int(stats[0].scan_bytes_streamed),
+        "_stream_ms": float(np.mean(stream_ms)),
+        "_streamed": float(np.mean([stats[(steps - 1 - b) % nb].scan_bytes_streamed for b in range(kept)])),
+    }
+    if stages:
+        # every stage, on a few more plain searches (seven event records per search)
+        idx.set_timing(1)
+        extra = min(steps, 8)
+        for i in range(extra):
+            idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores, stream=stream)
+        torch.cuda.synchronize()
+        stage_sum = {}
+        for back in range(extra):
+            for name, v in idx.stage_ms(back).items():
+                stage_sum[name] = stage_sum.get(name, 0.0) + v
+        rep["stages_ms"] = {name: v / extra for name, v in stage_sum.items()}
+        rep["stages_note"] = (f"plain ivf_search with events around every stage, {extra} searches after the timed "
+                              "region (the events add ~18 us per search)")
+        c = rep["stages_ms"]["coarse"]
+        rep["coarse_tflops_fp32"] = 2.0 * w.nq * w.nlist * w.d / (c * 1e-3) / 1e12 if c > 0 else 0.0
+    idx.set_timing(0)
+    return rep, q_host, q_dev, first, (out_ids, out_scores)
+
+
+def pcie_report(rep, direct, h2d):
+    streamed = rep["_streamed"]
+    t_stream = rep["scan"]["ms_per_launch"] if direct else rep["_stream_ms"]   # direct reads happen inside the scan
+    rate = streamed / 1e9 / (t_stream * 1e-3) if t_stream > 0 else None
+    return {"streamed_GB_per_batch": streamed / 1e9, "GBps_over_stream_stage": rate,
+            "mode": "scan reads pinned host memory directly" if direct else "hipMemcpyAsync to staging on a side stream",
+            "pinned_h2d_copy_GBps_1GiB": h2d, "frac_of_h2d_copy": rate / h2d if rate else None}
+
+
+def set_quarter_budget(idx, w, lw):
+    import numpy as np
+    lens = np.diff(lw.offsets)
+    order = np.lexsort((np.arange(w.nlist), -lens))
+    keep = order[: int(w.nlist * w.resident_list_frac)]
+    budget = int(((lens[keep] + 63) // 64).sum()) * 64 * w.row_bytes
+    idx.set_device_budget(budget)
+    log(f"device budget {budget / 2**30:.2f} GiB: {idx.info().resident_lists} lists resident")
+
+
+def public(rep):
+    return {k: v for k, v in rep.items() if not k.startswith("_")}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C5")
+    ap.add_argument("--others", default=None,
+                    help="comma-separated workloads measured afterwards and reported under other_configs "
+                         "(default: C1,C2,C3,C4 when the workload is C5 and no experiment flag is given; 'none' skips)")
     ap.add_argument("--batches", type=int, default=4, help="query batches rotated between steps")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 skips the CPU baseline")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
@@ -160,6 +321,9 @@ def main():
     ap.add_argument("--budget-change", action="store_true",
                     help="also time a change of the device budget (to a quarter of the lists and back), "
                          "blocking and in the background while searches go on")
+    ap.add_argument("--skew-components", type=int, default=0,
+                    help="draw every query batch from this many mixture components only (about nq/m queries "
+                         "then probe the same lists); 0 = the benchmark's uniform batches")
     ap.add_argument("--read-ceiling-gib", type=int, default=24,
                     help="size of the plain streaming-read measurement (0 skips it)")
     args = ap.parse_args()
@@ -173,6 +337,13 @@ def main():
     from paper_2504_15302_amd import workloads as W
     from paper_2504_15302_amd.loader import load_workload
 
+    experiment = bool(args.option or args.n or args.batch_sweep or args.k_sweep or args.budget_change
+                      or args.calibrate_copy_mib or args.skew_components)
+    if args.others is None:
+        others = ["C1", "C2", "C3", "C4"] if (args.workload == "C5" and not experiment) else []
+    else:
+        others = [o for o in args.others.split(",") if o and o != "none"]
+
     w = W.CONFIGS[args.workload]
     if args.n:
         w = W.scaled(w, n=args.n, name=w.name + f"-n{args.n}")
@@ -184,18 +355,9 @@ def main():
         name, val = opt.split("=")
         idx.set_option(name, int(val))
     if w.resident_list_frac is not None:
-        lens = np.diff(lw.offsets)
-        order = np.lexsort((np.arange(w.nlist), -lens))
-        keep = order[: int(w.nlist * w.resident_list_frac)]
-        budget = int(((lens[keep] + 63) // 64).sum()) * 64 * w.row_bytes
-        idx.set_device_budget(budget)
-        log(f"device budget {budget / 2**30:.2f} GiB: {idx.info().resident_lists} lists resident")
-
+        set_quarter_budget(idx, w, lw)
+    direct = not any(o.replace(" ", "") == "host_direct=0" for o in args.option)   # library default: direct
     nb = max(1, args.batches)
-    q_host = [W.queries(w, batch=b) for b in range(nb)]
-    q_dev = [torch.from_numpy(q).cuda() for q in q_host]
-    out_ids = torch.empty((w.nq, w.k), dtype=torch.int64, device="cuda")
-    out_scores = torch.empty((w.nq, w.k), dtype=torch.float32, device="cuda")
 
     if args.calibrate_copy_mib:
         nbytes = args.calibrate_copy_mib << 20
@@ -227,111 +389,47 @@ def main():
             log("no room for the read-ceiling buffer; skipped")
         torch.cuda.empty_cache()
 
-    idx.set_timing(2)
-    stats = []
-    first = None
-    for b in range(nb):                      # also the first warm-up of every batch
-        idx.search(q_dev[b], w.nprobe, w.k, out_ids, out_scores)
-        torch.cuda.synchronize()
-        stats.append(idx.last_search_stats())
-        if b == 0:
-            first = (out_ids.cpu().numpy().copy(), out_scores.cpu().numpy().copy())
-    for i in range(args.warmup):
-        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores)
-    torch.cuda.synchronize()
-
-    # timed region: only the scan (and the streaming of host lists) carries HIP events
-    idx.set_timing(2)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) / args.steps * 1e3
-    qps = w.nq / (ms_per_step / 1e3)
-
-    # the dominant kernel's duration over those same steps (HIP events on the search's stream)
-    direct = not any(o.replace(" ", "") == "host_direct=0" for o in args.option)   # library default: direct
-    kept = min(args.steps, 64)
-    scan_ms, scan_bytes, stream_ms = [], [], []
-    for back in range(kept):
-        step = args.steps - 1 - back
-        ms = idx.stage_ms(back)
-        st = stats[step % nb]
-        scan_ms.append(ms["scan"])
-        stream_ms.append(ms["stream"])
-        # with host lists read in place, the one scan launch covers both HBM and PCIe bytes
-        scan_bytes.append(st.scan_bytes if direct else st.scan_bytes_resident)
-
-    # every stage, on a few more steps outside the timed region (seven event records per search)
-    idx.set_timing(1)
-    extra = min(args.steps, 8)
-    for i in range(extra):
-        idx.search(q_dev[i % nb], w.nprobe, w.k, out_ids, out_scores)
-    torch.cuda.synchronize()
-    stage_sum = {}
-    for back in range(extra):
-        for name, v in idx.stage_ms(back).items():
-            stage_sum[name] = stage_sum.get(name, 0.0) + v
-    stage_avg = {name: v / extra for name, v in stage_sum.items()}
-    stage_avg["scan"] = float(np.mean(scan_ms))          # the timed steps' own figures where they exist
-    stage_avg["stream"] = float(np.mean(stream_ms))
-    avg_scan_ms = float(np.mean(scan_ms))
-    avg_scan_bytes = float(np.mean(scan_bytes))
-    achieved = avg_scan_bytes / (avg_scan_ms * 1e-3) / 1e9 if avg_scan_ms > 0 else 0.0
-    coarse_tflops = 2.0 * w.nq * w.nlist * w.d / (stage_avg["coarse"] * 1e-3) / 1e12 if stage_avg["coarse"] > 0 else 0.0
-
-    st0 = stats[0]
+    rep, q_host, q_dev, first, (out_ids, out_scores) = measure(idx, w, args.steps, args.warmup, nb, direct,
+                                                               components=args.skew_components or None)
+    sc = rep["scan"]
     result = {
         "metric": "queries/sec and list-scan HBM GB/s (% of peak), batched IVF top-k search",
-        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": rep["queries_per_s"], "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 accumulate over " + {"fp32": "f32", "fp16": "f16", "int8": "i8 codes + f32 scale"}[w.storage] + " storage",
         "data": "synthetic (seeded Gaussian mixture, generated on the GPU; random-init, no dataset)",
-        "config": {"workload": f"{w.name}: IVF-Flat inner product, N={w.n}, d={w.d}, {w.storage} storage, "
-                               f"nlist={w.nlist}, nq={w.nq}, nprobe={w.nprobe}, k={w.k}"
-                               + (f", {w.resident_list_frac:.0%} of lists HBM-resident" if w.resident_list_frac else ""),
+        "config": {"workload": workload_label(w),
                    "query_batches_rotated": nb,
-                   "unique_lists_per_batch": int(st0.unique_lists),
-                   "scan_bytes_per_batch": int(st0.scan_bytes),
-                   "scan_bytes_streamed_per_batch": int(st0.scan_bytes_streamed)},
+                   "unique_lists_per_batch": rep["unique_lists_per_batch"],
+                   "scan_bytes_per_batch": rep["scan_bytes_per_batch"],
+                   "scan_bytes_streamed_per_batch": rep["scan_bytes_streamed_per_batch"],
+                   "pairs_per_batch": rep["pairs_per_batch"],
+                   "queries_per_probed_list": rep["queries_per_probed_list"],
+                   "scan_requested_bytes_per_batch": rep["scan_requested_bytes_per_batch"],
+                   "skew_components": args.skew_components or None,
+                   "step": "one ivf_search_queued call; K calls issued back to back, one synchronisation at the end"},
         "roofline": {"bound": "hbm", "kernel": "k_scan (scan of HBM-resident probed lists)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES.get(w.name) if not args.option else None,
+                     "achieved": sc["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": sc["GBps"] / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES.get(w.name) if not experiment else None,
                      "traffic_source": TRAFFIC_SOURCE[w.name] + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
-                                       "bytes per launch)" if (w.name in TRAFFIC_BYTES and not args.option) else None,
-                     "bytes_per_launch": avg_scan_bytes, "ms_per_launch": avg_scan_ms,
-                     "launches_timed": kept,
+                                       "bytes per launch; a constant from that summary, not counted in this run)"
+                     if (w.name in TRAFFIC_BYTES and not experiment) else None,
+                     "bytes_per_launch": sc["bytes_per_launch"], "ms_per_launch": sc["ms_per_launch"],
+                     "launches_timed": sc["launches_timed"],
+                     "ms_per_launch_plain_search": sc["ms_per_launch_plain_search"],
+                     "achieved_plain_search": sc["GBps_plain_search"],
                      "plain_read_same_pattern_GBps": read_ceiling},
-        "stages_ms": stage_avg,
-        "stages_note": "scan and stream: HIP events inside the timed steps; the other stages: events on "
-                       f"{extra} further steps after the timed region",
-        "coarse_tflops_fp32": coarse_tflops,
+        "timing": rep["timing"],
+        "stages_ms": rep.get("stages_ms"),
+        "stages_note": rep.get("stages_note"),
+        "coarse_tflops_fp32": rep.get("coarse_tflops_fp32"),
         "index_build_seconds": lw.seconds,
     }
-    if st0.scan_bytes_streamed > 0:
-        # the box's own pinned host-to-device copy rate is the denominator for the streamed part
-        hsrc = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
-        ddst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-        ddst.copy_(hsrc, non_blocking=True)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(4):
-            ddst.copy_(hsrc, non_blocking=True)
-        e1.record()
-        torch.cuda.synchronize()
-        h2d = 4 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del hsrc, ddst
-        streamed = float(np.mean([stats[(args.steps - 1 - b) % nb].scan_bytes_streamed for b in range(kept)]))
-        t_stream = stage_avg["scan"] if direct else stage_avg["stream"]   # direct reads happen inside the scan
-        rate = streamed / 1e9 / (t_stream * 1e-3) if t_stream > 0 else None
+    if rep["scan_bytes_streamed_per_batch"] > 0:
         result["roofline"]["note"] = ("this workload is PCIe-bound: most probed bytes come from pinned host memory; "
                                       "see the pcie object, the HBM figure is not meaningful here")
-        result["pcie"] = {"streamed_GB_per_batch": streamed / 1e9, "GBps_over_stream_stage": rate,
-                          "mode": "scan reads pinned host memory directly" if direct else "hipMemcpyAsync to staging on a side stream",
-                          "pinned_h2d_copy_GBps_1GiB": h2d, "frac_of_h2d_copy": rate / h2d if rate else None}
+        result["pcie"] = pcie_report(rep, direct, pinned_h2d_rate())
     if args.batch_sweep:
         from paper_2504_15302_amd import ivf as ivf_mod
         sizes = [b for b in (8, 16, 32, 64, 128, 256) if b <= w.nq]
@@ -371,9 +469,43 @@ def main():
         result["budget_change"] = budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log)
     if args.cpu_seconds > 0:
         log("timing the CPU oracle on a sample of batch 0")
-        result["cpu_baseline"] = cpu_baseline(lw, idx, q_host[0], first[0], first[1], w.nprobe, w.k, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(lw, q_host[0], first[0], first[1], w.nprobe, w.k, args.cpu_seconds)
     else:
         result["cpu_baseline"] = None
+
+    if others:
+        idx.close()
+        del lw, idx, q_dev, out_ids, out_scores
+        torch.cuda.empty_cache()
+        result["other_configs"] = {}
+        built = {}                            # C4 is C3's index under a budget
+        h2d = None
+        for name in others:
+            ow = W.CONFIGS[name]
+            key = (ow.n, ow.d, ow.nlist, ow.storage, ow.seed)
+            if key not in built:
+                for olw in built.values():
+                    olw.index.close()
+                built.clear()
+                torch.cuda.empty_cache()
+                log(f"building {ow.name}: {ow.n} x {ow.d} {ow.storage}, nlist {ow.nlist}")
+                built[key] = load_workload(ow, groups_per_chunk=32, log=log)
+            olw = built[key]
+            if ow.resident_list_frac is not None:
+                set_quarter_budget(olw.index, ow, olw)
+            else:
+                olw.index.set_device_budget(2**62)
+            orep, _, _, _, _ = measure(olw.index, ow, args.steps, args.warmup, nb, True)
+            entry = {"workload": workload_label(ow)}
+            entry.update(public(orep))
+            if orep["scan_bytes_streamed_per_batch"] > 0:
+                h2d = h2d or pinned_h2d_rate()
+                entry["pcie"] = pcie_report(orep, True, h2d)
+                entry["scan"]["note"] = "PCIe-bound: see pcie; the HBM fraction is not meaningful here"
+            result["other_configs"][name] = entry
+            log(f"{name}: {entry['queries_per_s']:.0f} queries/s queued, scan {entry['scan']['GBps']:.0f} GB/s")
+        for olw in built.values():
+            olw.index.close()
     print(json.dumps(result), flush=True)
 
 

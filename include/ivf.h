@@ -20,7 +20,10 @@
  *   - The library COPIES what it is given at upload; the caller keeps ownership of
  *     its buffers and may free them when the call returns.
  *   - One search (or upload, or budget change) at a time per index: calls on the
- *     same index must not overlap.  Different indexes are independent.
+ *     same index must not overlap on the host.  On the device, consecutive searches of
+ *     an index share scratch memory; the library orders them itself (a search issued on
+ *     another stream than the one before it starts behind that one), so any stream may
+ *     be passed to any call.  Different indexes are independent.
  *   - Limits: d a multiple of 8 (16 for IVF_INT8) and d <= 4096; 1 <= k <= 1024;
  *     1 <= nprobe <= 1024 (nprobe above nlist is clamped to nlist); nq <= 65535 per
  *     call; n < 2^32; nlist < 2^28; a list holds at most 65535 * 64 vectors.
@@ -58,7 +61,25 @@ typedef enum {
  * embeddings (choice of scale, rounding) is data preparation by the caller, like the
  * assignment to lists: the search is exact over the vectors the records stand for.
  */
-enum { IVF_FP32 = 0, IVF_FP16 = 1, IVF_INT8 = 2 };
+enum { IVF_FP32 = 0, IVF_FP16 = 1, IVF_INT8 = 2, IVF_PQ8 = 3 };
+
+/*
+ * IVF_PQ8: lists of product-quantisation codes, the kind of code the paper's on-disk index
+ * variant keeps in memory (Section 6.5 "On-Disk Index"; the paper fixes no format, this one
+ * is the build's own).  The d dimensions are cut into m subspaces of d/m consecutive
+ * dimensions; subspace j has a codebook of 256 codewords; a stored vector is m one-byte
+ * codes and stands for the concatenation of the codewords they select, so that
+ *     score(q, i) = sum_j <q_j, codebook[j][code_ij]>        (fp32, ascending j)
+ * Training the codebooks and encoding the embeddings are data preparation by the caller,
+ * like the centroids and the assignment to lists: the search is exact over the vectors
+ * the codes stand for.
+ *   codebooks  [m, 256, d/m] fp32, host or device; copied.  m a multiple of 16, m <= 128,
+ *              d a multiple of m.
+ * Call it before an upload with dtype IVF_PQ8 (whose `vectors` are then [n, m] bytes); the
+ * codebooks stay until they are set again.  Host-resident code lists are read in place
+ * only (ivf_search returns IVF_ERR_INVALID in the staged mode, "host_direct" = 0).
+ */
+int ivf_index_set_pq_codebooks(ivf_index *idx, int d, int m, const float *codebooks);
 
 /* Creates an empty index bound to the current HIP device. */
 int ivf_index_create(ivf_index **out);
@@ -74,7 +95,8 @@ void ivf_index_destroy(ivf_index *idx);
  *   n             number of stored vectors
  *   centroids     [nlist, d] fp32 row-major, host or device
  *   vectors       [n, d] row-major in list order, fp32 or IEEE binary16 per `dtype`
- *                 (IVF_INT8: [n] records of d+4 bytes, see above), host or device
+ *                 (IVF_INT8: [n] records of d+4 bytes, IVF_PQ8: [n, m] code bytes, see
+ *                 above), host or device
  *   ids           [n] user ids in the same order, host or device
  *   list_offsets  [nlist+1], list j owns rows [list_offsets[j], list_offsets[j+1]);
  *                 list_offsets[0] = 0, list_offsets[nlist] = n; host or device
@@ -181,6 +203,36 @@ int ivf_budget_wait(ivf_index *idx);
 int ivf_search(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int k,
                int64_t *out_ids, float *out_scores, void *stream);
 
+/*
+ * ivf_search_queued — the same search for callers that queue searches back to back (a
+ * serving loop, the retrieval worker): results are identical to ivf_search's, but the
+ * stages of consecutive searches overlap.  The paper keeps its accelerator busy by
+ * starting the next items on streams of their own while the current one is still being
+ * worked on (Section 4.3 "LLM Prefetching Pipeline"); here the coarse quantisation, probe
+ * selection and regrouping of search i+1 run under the list scan of search i, and the
+ * final selection of search i (on the caller's stream) under the scan of search i+1.  The
+ * library uses three streams of its own (two for the front stages, one for the scans) and
+ * three sets of scratch memory taken in turn.
+ *   queries_ready  hipEvent_t after which `queries` may be read, or NULL if it may be
+ *                  read as soon as the call is made.  Unlike ivf_search, the call does NOT
+ *                  order its reading of `queries` behind earlier work on `stream`: that
+ *                  is what lets it start under the previous search.  `queries` must stay
+ *                  unchanged until the search is done.
+ *   stream         the final selection runs on it, behind the scan: the outputs are valid
+ *                  once the caller has synchronised it, and work the caller queued on it
+ *                  before the call (say, a copy out of out_ids) precedes the writes to
+ *                  out_ids / out_scores.
+ * While a budget change is under way, in the staged host-list mode, with timing level 1,
+ * and when the lists to scan are bounded by less than "queue_min_mb" MiB (default 256:
+ * the overlap cannot repay a dozen extra stream and event calls) the search runs exactly
+ * like ivf_search, behind queries_ready.  Everything else is as for ivf_search: same
+ * limits, same scratch growth on first use (of each of the three sets).  Pass a stream
+ * of your own rather than the legacy default stream (NULL), whose implicit
+ * synchronisation with other streams costs most of the overlap.
+ */
+int ivf_search_queued(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int k,
+                      int64_t *out_ids, float *out_scores, void *stream, void *queries_ready);
+
 /* Thread-local message of the last error on this thread ("" if none). */
 const char *ivf_last_error(void);
 
@@ -261,10 +313,15 @@ int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
 
 /* Tuning knobs; unknown names or values return IVF_ERR_INVALID.  Defaults are the tuned
    values.  "host_direct" 0|1 (see ivf_set_device_budget), "stage_mb" 1..4096, "nstage"
-   2..8, "nside" 1..4 (copy streams of the staged mode), "scan_unroll" 8|16 (16-byte
+   2..8, "nside" 1..4 (copy streams of the staged mode: the copies of a chunk go round
+   them), "scan_unroll" 8|16 (16-byte
    loads per lane and register buffer), "scan_waves" 1|2|4|8 (wavefronts per workgroup),
-   "scan_mode" 0|1 (1 = persistent wavefronts on an atomic queue, "scan_wgs_per_cu"
-   1..16), "scan_prune" 0|1|2 (store pruning off / on for large plans / always),
+   "scan_split" 0|1|2|4 (wavefronts that share one 64-vector block, each taking a slice of the
+   dimensions; 0 = as many as leave each a share of 48 KiB, fixed per index; partial sums are
+   added in LDS, so scores may differ in the last bit between settings), "queue_min_mb" (see
+   ivf_search_queued), "queue_fronts" 0|1|2 (streams that the front stages of queued searches
+   alternate between; 0 = two behind short scans, one behind long ones),
+   "scan_prune" 0|1|2 (store pruning off / on for large plans / always),
    "regroup_fused" 0|1 (1 = searches with at most 1024 lists and 2048 (query, list) pairs
    regroup in a single launch), "sel_threads" 0|256|1024 (workgroup size of the selection kernels; 0 = by problem size),
    "residency_policy" 0|1 and "segment_mb" (see ivf_set_device_budget; the segment size

@@ -7,14 +7,15 @@
 namespace {
 
 void free_scratch(Scratch& s) {
+    const hipEvent_t end = s.end;                // the index's, not the buffers'
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
     dfree(s.sblk_start); dfree(s.item_start); dfree(s.wg_totals); dfree(s.pair_flat);
     dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
-    dfree(s.scores); dfree(s.bmax);
+    dfree(s.scores); dfree(s.bmax); dfree(s.pq_tables);
     if (s.h_probes) (void)hipHostFree(s.h_probes);
     if (s.h_items) (void)hipHostFree(s.h_items);
-    if (s.h_counters) (void)hipHostFree(s.h_counters);
     s = Scratch();
+    s.end = end;
 }
 
 void free_staging(ivf_index* x) {
@@ -36,7 +37,9 @@ void free_index_data(ivf_index* x) {
     pool_free_all(x->dpool);
     pool_free_all(x->hpool);
     free_staging(x);
-    free_scratch(x->sc);
+    for (int p = 0; p < kSets; ++p) free_scratch(x->sc[p]);
+    x->last_sc = nullptr;
+    x->last_nq = 0;
     x->ready = x->uploading = false;
     x->resident_lists = 0;
 }
@@ -60,8 +63,7 @@ int64_t block_bound(const ivf_index* x, int64_t nq, int nprobe) {
     return nq * x->top_nblk_prefix[p];
 }
 
-int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
-    Scratch& s = x->sc;
+int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offload) {
     const int64_t ntile = (x->nlist + kCoarseTile - 1) / kCoarseTile;
     const size_t npairs = (size_t)nq * nprobe;
     const size_t nblocks = (size_t)std::max<int64_t>(1, block_bound(x, nq, nprobe));
@@ -87,8 +89,6 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
         if ((rc = dalloc(s.sblk_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.item_start, (size_t)x->nlist, s.bytes))) return rc;
         s.cap_nlist = x->nlist;
-        if (!s.h_counters)
-            HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&s.h_counters), sizeof(unsigned long long) * kNumCounters));
     }
     if (npairs > s.cap_pairs) {
         if ((rc = dalloc(s.probes, npairs, s.bytes))) return rc;
@@ -101,6 +101,10 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
         if ((rc = dalloc(s.scores, nblocks * kLanes, s.bytes))) return rc;
         if ((rc = dalloc(s.bmax, nblocks, s.bytes))) return rc;
         s.cap_blocks = nblocks;
+    }
+    if (x->dtype == IVF_PQ8 && (size_t)nq > s.cap_pq_q) {
+        if ((rc = dalloc(s.pq_tables, (size_t)nq * x->pq_m * 256, s.bytes))) return rc;
+        s.cap_pq_q = (size_t)nq;
     }
     if (offload) {
         if (nblocks > s.cap_stream_items) {
@@ -129,41 +133,92 @@ int ensure_scratch(ivf_index* x, int64_t nq, int nprobe, bool offload) {
     return 0;
 }
 
+// One search as the launch sequence sees it.
+struct SearchCtx {
+    const float* Q = nullptr;
+    int64_t nq = 0;
+    int nprobe = 0, k = 0;
+    int64_t* out_ids = nullptr;
+    float* out_scores = nullptr;
+    int nlist = 0, ntile = 0, npairs = 0;
+    bool offload = false;              // host-resident lists are copied to staging buffers
+    bool moving = false;               // a budget change was under way when the search was issued
+    int prune_blocks = 0, prune_j = 0; // bound kept by the scan (see k_scan)
+    // Events tied to the scan kernel's own start and end (either may be null).  Bound to the
+    // dispatch itself, they cost no packet of their own on the stream, unlike a recorded
+    // event, and read the kernel's duration without the launch gap around it.
+    hipEvent_t scan_start = nullptr, scan_stop = nullptr;
+};
+
 template <int ST, int U, int WAVES>
-void launch_scan_k(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
-                   const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
-    Scratch& s = x->sc;
-    unsigned int* queue = reinterpret_cast<unsigned int*>(s.zeroed + 2 * (size_t)x->nlist);
-    dim3 grid = mode == 0 ? dim3((unsigned)((work_items + WAVES - 1) / WAVES))
-                          : dim3((unsigned)(x->cus * std::max<int64_t>(1, x->opt_scan_wgs_per_cu)));
-    hipLaunchKernelGGL((k_scan<ST, U, WAVES>), grid, dim3(WAVES * 64), 0, st, items, n_dev, n_host, Q, x->d,
-                       s.scores, s.bmax, mode, queue, s.qthr, x->prune_blocks, x->prune_j);
+void launch_scan_k(ivf_index* x, Scratch& s, const SearchCtx& c, size_t work_items, hipStream_t st, const ScanItem* items,
+                   const unsigned long long* n_dev, uint32_t n_host, const float* Q) {
+    const dim3 grid((unsigned)((work_items + WAVES - 1) / WAVES));
+    hipExtLaunchKernelGGL((k_scan<ST, U, WAVES>), grid, dim3(WAVES * 64), 0, st, c.scan_start, c.scan_stop, 0, items, n_dev,
+                          n_host, Q, x->d, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
 }
 
 template <int ST, int U>
-void launch_scan_w(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
-                   const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
+void launch_scan_w(ivf_index* x, Scratch& s, const SearchCtx& c, size_t work_items, hipStream_t st, const ScanItem* items,
+                   const unsigned long long* n_dev, uint32_t n_host, const float* Q) {
     switch ((int)x->opt_scan_waves) {
-        case 1: launch_scan_k<ST, U, 1>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        case 2: launch_scan_k<ST, U, 2>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        case 8: launch_scan_k<ST, U, 8>(x, work_items, st, items, n_dev, n_host, Q, mode); break;
-        default: launch_scan_k<ST, U, 4>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        case 1: launch_scan_k<ST, U, 1>(x, s, c, work_items, st, items, n_dev, n_host, Q); break;
+        case 2: launch_scan_k<ST, U, 2>(x, s, c, work_items, st, items, n_dev, n_host, Q); break;
+        case 8: launch_scan_k<ST, U, 8>(x, s, c, work_items, st, items, n_dev, n_host, Q); break;
+        default: launch_scan_k<ST, U, 4>(x, s, c, work_items, st, items, n_dev, n_host, Q);
     }
 }
 
-// work_items: number of items (mode 0: an upper bound is enough, excess wavefronts exit)
-void launch_scan(ivf_index* x, size_t work_items, hipStream_t st, const ScanItem* items,
-                 const unsigned long long* n_dev, uint32_t n_host, const float* Q, int mode) {
+// Wavefronts that share one block.  By default a wavefront's share is kept at 48 KiB or
+// more (shorter shares lose to the fixed cost per item): a function of the stored vector's
+// size alone, so that an index always adds its partial sums in the same order.
+int scan_split_of(const ivf_index* x) {
+    if (x->opt_scan_split) return (int)x->opt_scan_split;
+    const size_t share = (size_t)48 << 10;
+    return x->block_bytes >= 4 * share ? 4 : x->block_bytes >= 2 * share ? 2 : 1;
+}
+
+template <int ST, int SPLIT>
+void launch_scan_split(ivf_index* x, Scratch& s, const SearchCtx& c, size_t work_items, hipStream_t st, const ScanItem* items,
+                       const unsigned long long* n_dev, uint32_t n_host, const float* Q) {
+    constexpr int per_wg = 4 / SPLIT;                        // items per workgroup of four wavefronts
+    const dim3 grid((unsigned)((work_items + per_wg - 1) / per_wg));
+    const int chunks = x->d / Store<ST>::E / SPLIT;          // per wavefront (the shorter share if uneven)
+    // the widest register buffers that the share of a wavefront fills without a remainder
+    if (chunks % 16 == 0 && x->opt_scan_unroll == 16)
+        hipExtLaunchKernelGGL((k_scan_split<ST, 16, SPLIT>), grid, dim3(256), 0, st, c.scan_start, c.scan_stop, 0, items, n_dev,
+                              n_host, Q, x->d, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
+    else
+        hipExtLaunchKernelGGL((k_scan_split<ST, 8, SPLIT>), grid, dim3(256), 0, st, c.scan_start, c.scan_stop, 0, items, n_dev,
+                              n_host, Q, x->d, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
+}
+
+template <int ST>
+void launch_scan_split_s(ivf_index* x, Scratch& s, const SearchCtx& c, size_t work_items, hipStream_t st, const ScanItem* items,
+                         const unsigned long long* n_dev, uint32_t n_host, const float* Q) {
+    if (scan_split_of(x) == 2) launch_scan_split<ST, 2>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+    else launch_scan_split<ST, 4>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+}
+
+// work_items: number of items (an upper bound is enough, excess wavefronts exit)
+void launch_scan(ivf_index* x, Scratch& s, const SearchCtx& c, size_t work_items, hipStream_t st, const ScanItem* items,
+                 const unsigned long long* n_dev, uint32_t n_host, const float* Q) {
     const int U = (int)x->opt_scan_unroll;
+    if (scan_split_of(x) > 1) {                    // several wavefronts per item
+        if (x->dtype == IVF_FP16) launch_scan_split_s<kF16>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        else if (x->dtype == IVF_INT8) launch_scan_split_s<kI8>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        else launch_scan_split_s<kF32>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        return;
+    }
     if (x->dtype == IVF_FP16) {
-        if (U == 8) launch_scan_w<kF16, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
-        else launch_scan_w<kF16, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        if (U == 8) launch_scan_w<kF16, 8>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        else launch_scan_w<kF16, 16>(x, s, c, work_items, st, items, n_dev, n_host, Q);
     } else if (x->dtype == IVF_INT8) {
-        if (U == 8) launch_scan_w<kI8, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
-        else launch_scan_w<kI8, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        if (U == 8) launch_scan_w<kI8, 8>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        else launch_scan_w<kI8, 16>(x, s, c, work_items, st, items, n_dev, n_host, Q);
     } else {
-        if (U == 8) launch_scan_w<kF32, 8>(x, work_items, st, items, n_dev, n_host, Q, mode);
-        else launch_scan_w<kF32, 16>(x, work_items, st, items, n_dev, n_host, Q, mode);
+        if (U == 8) launch_scan_w<kF32, 8>(x, s, c, work_items, st, items, n_dev, n_host, Q);
+        else launch_scan_w<kF32, 16>(x, s, c, work_items, st, items, n_dev, n_host, Q);
     }
 }
 
@@ -191,8 +246,10 @@ int ensure_staging(ivf_index* x) {
 // The host-resident part of a search: mirror the device's pair numbering, pack the
 // probed host lists into staging-sized chunks, copy each chunk on the side stream and
 // scan it on the caller's stream as soon as it has landed.
-int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipStream_t st) {
-    Scratch& s = x->sc;
+int stream_host_lists(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    const float* Q = c.Q;
+    const int64_t nq = c.nq;
+    const int nprobe = c.nprobe;
     HIP_TRY(hipEventSynchronize(x->ev_probes));
     const int nside = (int)std::min<int64_t>(kMaxSide, std::max<int64_t>(1, x->opt_nside));
     for (int i = 0; i < kMaxSide; ++i) HIP_TRY(hipStreamSynchronize(x->side[i]));   // pinned item mirror of the previous search is free
@@ -235,7 +292,6 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
     int chunk = 0;
     while (i < hl.size()) {
         const int slot = chunk % x->nstage;
-        hipStream_t side = x->side[chunk % nside];
         size_t used = 0, j = i;
         while (j < hl.size()) {
             size_t b = (size_t)x->nblk[hl[j].l] * x->block_bytes;
@@ -244,12 +300,18 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
             ++j;
         }
         if (j == i) return fail(IVF_ERR_LIMIT, "staging buffer smaller than a list");
-        if (x->stage_used[slot]) HIP_TRY(hipStreamWaitEvent(side, x->stage_free[slot], 0));
+        // The copies of a chunk go round the copy streams: a copy of one list (~2 MB) is too
+        // short to reach the link's rate by itself, two or three of them side by side do.
+        if (x->stage_used[slot])
+            for (int sd = 0; sd < nside; ++sd) HIP_TRY(hipStreamWaitEvent(x->side[sd], x->stage_free[slot], 0));
         // copies: merge lists that are neighbours in the host arena
         size_t dst_off = 0;
         size_t a = i;
         const size_t item_begin = item_off;
+        int ncopy = 0;
         while (a < j) {
+            hipStream_t side = x->side[ncopy % nside];
+            ++ncopy;
             const char* src = x->host_ptr[hl[a].l];
             size_t bytes = (size_t)x->nblk[hl[a].l] * x->block_bytes;
             size_t e = a + 1;
@@ -285,10 +347,12 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
         }
         const size_t nitems = item_off - item_begin;
         HIP_TRY(hipMemcpyAsync(s.stream_items + item_begin, s.h_items + item_begin,
-                               nitems * sizeof(ScanItem), hipMemcpyHostToDevice, side));
-        HIP_TRY(hipEventRecord(x->stage_ready[slot], side));
-        HIP_TRY(hipStreamWaitEvent(st, x->stage_ready[slot], 0));
-        launch_scan(x, nitems, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q, 0);
+                               nitems * sizeof(ScanItem), hipMemcpyHostToDevice, x->side[ncopy % nside]));
+        for (int sd = 0; sd < std::min(nside, ncopy + 1); ++sd) {
+            HIP_TRY(hipEventRecord(x->stage_ready[slot][sd], x->side[sd]));
+            HIP_TRY(hipStreamWaitEvent(st, x->stage_ready[slot][sd], 0));
+        }
+        launch_scan(x, s, c, nitems, st, s.stream_items + item_begin, nullptr, (uint32_t)nitems, Q);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(x->stage_free[slot], st));
         x->stage_used[slot] = true;
@@ -302,6 +366,248 @@ int stream_host_lists(ivf_index* x, const float* Q, int64_t nq, int nprobe, hipS
 int check_ready(const ivf_index* x) {
     if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
     if (!x->ready) return fail(IVF_ERR_INVALID, "index has no uploaded data");
+    return 0;
+}
+
+// Argument checks shared by the search entry points.  Returns a negative error, 1 if there
+// is nothing to do (nq = 0), 0 otherwise with `c` filled in.
+int search_args(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
+                float* out_scores, SearchCtx& c) {
+    int rc = check_ready(x);
+    if (rc) return rc;
+    if (nq < 0) return fail(IVF_ERR_INVALID, "nq must be non-negative");
+    if (nq == 0) return 1;
+    if (!queries || !out_ids || !out_scores) return fail(IVF_ERR_INVALID, "queries, out_ids or out_scores is NULL");
+    if (nprobe <= 0 || k <= 0) return fail(IVF_ERR_INVALID, "nprobe and k must be positive");
+    if (k > kMaxK) return fail(IVF_ERR_LIMIT, "k above %d", kMaxK);
+    if (nprobe > x->nlist) nprobe = (int)x->nlist;
+    if (nprobe > kMaxK) return fail(IVF_ERR_LIMIT, "nprobe above %d", kMaxK);
+    if (nq > 65535) return fail(IVF_ERR_LIMIT, "nq above 65535");
+    if ((uint64_t)nq * (uint64_t)nprobe >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "nq*nprobe above 2^31");
+    if ((uint64_t)block_bound(x, nq, nprobe) >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "batch too large for one call");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != x->device)
+        return fail(IVF_ERR_INVALID, "the index lives on HIP device %d but the current device is %d", x->device, dev);
+    c.Q = queries; c.nq = nq; c.nprobe = nprobe; c.k = k; c.out_ids = out_ids; c.out_scores = out_scores;
+    c.nlist = (int)x->nlist;
+    c.ntile = (c.nlist + kCoarseTile - 1) / kCoarseTile;
+    c.npairs = (int)(nq * nprobe);
+    c.offload = x->resident_lists < x->nlist && !x->opt_host_direct;
+    if (x->dtype == IVF_PQ8 && c.offload)
+        return fail(IVF_ERR_INVALID, "product-quantised lists in pinned host memory are read in place: "
+                                     "the staged mode (host_direct = 0) does not take them");
+    return 0;
+}
+
+// Searches share scratch memory: a search starts behind the event that the last user of
+// its scratch set left behind its last kernel (no host wait; nothing at all when that
+// event was recorded on the same stream).  The stream of an earlier search is never
+// touched again: the caller may have destroyed it.  `first` is the stream of this search's
+// first kernel, `st` the caller's.
+bool stream_is_capturing(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return cs == hipStreamCaptureStatusActive;
+}
+
+int order_after_last_use(Scratch& s, hipStream_t st, hipStream_t first) {
+    if (!s.end_recorded) return 0;
+    if (stream_is_capturing(st)) return 0;            // a captured search is kernel launches only; its place among
+                                                      // the other searches is where the caller launches the graph
+    HIP_TRY(hipStreamWaitEvent(first, s.end, 0));
+    return 0;
+}
+
+// What a search on one stream does before its first kernel.
+int search_prologue(ivf_index* x, hipStream_t st, SearchCtx& c) {
+    int rc;
+    c.moving = moves_active(x);
+    if (c.moving) {
+        // a budget change is under way: take over what has landed, issue more copies, and
+        // let this search start only behind the latest update of the address table
+        if ((rc = moves_advance(x))) return rc;
+        if (!x->limbo.empty()) HIP_TRY(hipStreamWaitEvent(st, x->limbo.back().after, 0));
+    }
+    c.offload = x->resident_lists < x->nlist && !x->opt_host_direct;
+    if (x->dtype == IVF_PQ8 && c.offload)
+        return fail(IVF_ERR_INVALID, "product-quantised lists in pinned host memory are read in place: "
+                                     "the staged mode (host_direct = 0) does not take them");
+    if (c.offload && (rc = ensure_staging(x))) return rc;
+    return 0;
+}
+
+// Running lower bound of each query's k-th best score, kept by the scan so that it can
+// skip storing blocks that cannot matter: from one block's k-th largest value (k <= 64) or
+// from the two best blocks' ceil(k/2)-th largest (k <= 128).  Small plans run as one wave
+// of work items, where nothing has a bound to prune by yet.
+void search_set_pruning(const ivf_index* x, SearchCtx& c) {
+    const bool small_plan = x->opt_scan_prune != 2 && block_bound(x, c.nq, c.nprobe) < 32768;
+    if (!x->opt_scan_prune || c.k > 128 || small_plan) { c.prune_blocks = 0; c.prune_j = 0; }
+    else if (c.k <= 64) { c.prune_blocks = 1; c.prune_j = c.k; }
+    else { c.prune_blocks = 2; c.prune_j = (c.k + 1) / 2; }
+}
+
+void enqueue_coarse(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    const int nz = (int)(2 * (size_t)c.nlist + 16 + 2 * kNumCounters + 2 * (size_t)c.nq);   // cleared by the coarse kernel
+    // Query rows per wavefront: as many as possible (each centroid row is then fetched
+    // once), but few enough that the grid still offers every SIMD a wavefront.
+    dim3 grid((unsigned)((c.nlist + kCoarseNT - 1) / kCoarseNT), 1);
+    const int64_t simds = (int64_t)x->cus * 4, waves_x = (int64_t)grid.x * 4;
+    const int64_t nq = c.nq;
+    int mt = nq > 64 ? 4 : nq > 32 ? 2 : 1;
+    while (mt > 1 && waves_x * ((nq + 32 * mt - 1) / (32 * mt)) < simds) mt >>= 1;
+    grid.y = (unsigned)((nq + 32 * mt - 1) / (32 * mt));
+    if (mt == 1)
+        hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, c.Q, x->d_centroids, s.S, s.tmax, (int)nq, c.nlist, x->d, c.ntile, s.zeroed, nz);
+    else if (mt == 2)
+        hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, c.Q, x->d_centroids, s.S, s.tmax, (int)nq, c.nlist, x->d, c.ntile, s.zeroed, nz);
+    else
+        hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, c.Q, x->d_centroids, s.S, s.tmax, (int)nq, c.nlist, x->d, c.ntile, s.zeroed, nz);
+}
+
+// The selection kernels are chains of barriers and dependent loads: with little to select
+// from, a workgroup of 4 wavefronts gets through them faster than one of 16.
+void enqueue_probe_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    int* hist = s.zeroed;
+    const bool small_probe = x->opt_sel_threads ? x->opt_sel_threads == 256 : c.ntile <= 128;
+    if (small_probe)
+        hipLaunchKernelGGL((k_probe_select<256>), dim3((unsigned)c.nq), dim3(256), 0, st, s.S, s.tmax, c.nlist, c.ntile, c.nprobe,
+                           s.probes, hist);
+    else
+        hipLaunchKernelGGL((k_probe_select<kSelThreads>), dim3((unsigned)c.nq), dim3(kSelThreads), 0, st, s.S, s.tmax, c.nlist,
+                           c.ntile, c.nprobe, s.probes, hist);
+}
+
+void enqueue_regroup(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st, bool under_a_scan) {
+    int* hist = s.zeroed;
+    int* cursor = s.zeroed + c.nlist;
+    const int nlist = c.nlist, npairs = c.npairs, nprobe = c.nprobe;
+    // One launch instead of four pays up to 1024 lists when the kernels have the GPU to
+    // themselves.  Under the scan of another search every launch waits tens of
+    // microseconds for room on a compute unit, so the single workgroup wins up to four
+    // times that size.
+    const int fuse = under_a_scan ? 4 : 1;
+    if (x->opt_regroup_fused && nlist <= fuse * kFusedMaxLists && npairs <= fuse * kFusedMaxPairs) {
+        // few lists and pairs: one workgroup does the whole regrouping in one launch
+        hipLaunchKernelGGL(k_regroup_small, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                           nlist, nprobe, x->block_bytes, s.probes, npairs, cursor, s.pair_start, s.sblk_start,
+                           s.item_start, s.pair_flat, s.pair_of_probe, s.items, x->d_hits, s.counters);
+    } else {
+        const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
+        hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                           nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
+        hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, hist, nlist, (int)wgs, s.wg_totals,
+                           s.pair_start, s.sblk_start, s.item_start);
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
+                           s.pair_start, cursor, s.pair_flat);
+        hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
+                           x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
+                           s.pair_flat, s.pair_of_probe, s.items, x->d_hits);
+    }
+}
+
+// The scan of every list the kernel can read (HBM-resident, or pinned host memory read in place).
+void enqueue_scan_kernels(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st);
+
+// c.scan_start / c.scan_stop, if set, end up around the scan: bound to the kernel where one
+// kernel does the scan, recorded on the stream otherwise.
+void enqueue_scan(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    const bool one_kernel = x->dtype != IVF_PQ8 && (x->resident_lists > 0 || x->opt_host_direct);
+    if (!one_kernel && c.scan_start) (void)hipEventRecord(c.scan_start, st);
+    enqueue_scan_kernels(x, s, c, st);
+    if (!one_kernel && c.scan_stop) (void)hipEventRecord(c.scan_stop, st);
+}
+
+void enqueue_scan_kernels(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    if (x->dtype == IVF_PQ8) {
+        // product-quantised lists: the queries' tables against the codebooks, then one
+        // workgroup per (query, list) pair gathers from its query's table in LDS
+        hipLaunchKernelGGL(k_pq_tables, dim3((unsigned)x->pq_m, (unsigned)c.nq), dim3(256), 0, st, c.Q, x->d_codebooks,
+                           s.pq_tables, x->d, x->pq_m);
+        hipLaunchKernelGGL(k_pq_scan, dim3((unsigned)c.npairs), dim3(kPqThreads), (size_t)x->pq_m * 1024, st, s.pair_flat,
+                           s.probes, s.pair_start, s.sblk_start, x->d_nblk, x->d_len, x->d_list_ptr, c.nprobe, x->pq_m,
+                           s.pq_tables, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
+        return;
+    }
+    if (x->resident_lists > 0 || x->opt_host_direct) {
+        const int64_t bound = std::max<int64_t>(1, block_bound(x, c.nq, c.nprobe));
+        launch_scan(x, s, c, (size_t)bound, st, s.items, s.counters + kCntItems, 0, c.Q);
+    }
+}
+
+void enqueue_final_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+    const bool small_final = x->opt_sel_threads ? x->opt_sel_threads == 256 : block_bound(x, 1, c.nprobe) <= 128;
+    ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
+    if (small_final)
+        hipLaunchKernelGGL((k_final_select<256>), dim3((unsigned)c.nq), dim3(256), 0, st, s.probes, s.pair_of_probe,
+                           s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, c.nprobe, c.k,
+                           c.prune_blocks ? s.qthr : nullptr, c.out_ids, c.out_scores);
+    else
+        hipLaunchKernelGGL((k_final_select<kSelThreads>), dim3((unsigned)c.nq), dim3(kSelThreads), 0, st, s.probes,
+                           s.pair_of_probe, s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos,
+                           x->d_id_sorted, c.nprobe, c.k, c.prune_blocks ? s.qthr : nullptr, c.out_ids, c.out_scores);
+}
+
+void search_epilogue(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st, bool queued) {
+    x->last_sc = &s;
+    x->last_nq = (int)c.nq;
+    x->last_nprobe = c.nprobe;
+    x->last_stream = st;
+    x->last_offload = c.offload;
+    x->last_queued = queued;
+}
+
+// The whole search as one chain of kernels on the caller's stream.
+int search_serial(ivf_index* x, Scratch& s, SearchCtx& c, hipStream_t st) {
+    int rc;
+    search_set_pruning(x, c);
+    const int tm = x->timing;                  // 0 off, 1 every stage, 2 the scan and streaming stages only
+    hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
+    int evi = 0;
+    auto mark = [&]() {
+        if (tm == 1 || (tm == 2 && evi >= 3 && evi <= 5)) (void)hipEventRecord(evs[evi], st);
+        ++evi;
+    };
+    mark();   // 0
+    enqueue_coarse(x, s, c, st);
+    mark();   // 1
+    enqueue_probe_select(x, s, c, st);
+    mark();   // 2
+    if (c.offload) {
+        HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)c.npairs, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipEventRecord(x->ev_probes, st));
+    }
+    enqueue_regroup(x, s, c, st, false);
+    if (tm) { c.scan_start = evs[3]; c.scan_stop = evs[4]; }     // events 3 and 4 sit on the scan itself
+    evi += 2;
+    enqueue_scan(x, s, c, st);
+    c.scan_start = c.scan_stop = nullptr;
+    HIP_TRY(hipGetLastError());
+    if (c.offload) {
+        if ((rc = stream_host_lists(x, s, c, st))) return rc;
+    }
+    mark();   // 5
+    enqueue_final_select(x, s, c, st);
+    mark();   // 6
+    HIP_TRY(hipGetLastError());
+    if (c.offload) {
+        HIP_TRY(hipEventRecord(x->ev_done, st));
+        x->done_recorded = true;
+    }
+    // behind the last kernel: the next search on another stream starts after it, and old
+    // places of moved lists are released only behind the searches that may read them
+    // (not under stream capture: the captured search stays a chain of kernels)
+    const bool moving = c.moving || moves_active(x);
+    if (moving || !stream_is_capturing(st)) {
+        HIP_TRY(hipEventRecord(s.end, st));
+        s.end_recorded = true;
+        if (moving) x->search_end_recorded = true;      // s is set 0 then, whose event is ev_search_end
+    }
+    search_epilogue(x, s, c, st, false);
+    if (tm) {
+        x->ev_queued[x->timed_searches % kTimingSlots] = false;
+        x->timed_searches += 1;
+    }
     return 0;
 }
 
@@ -323,12 +629,22 @@ int ivf_index_create(ivf_index** out) {
     for (int i = 0; e == hipSuccess && i < kMaxSide; ++i) e = hipStreamCreateWithFlags(&x->side[i], hipStreamNonBlocking);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->move_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->patch_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->pipe_scan, hipStreamNonBlocking);
+    for (int i = 0; e == hipSuccess && i < 2; ++i) e = hipStreamCreateWithFlags(&x->pipe_front[i], hipStreamNonBlocking);
+    for (int i = 0; e == hipSuccess && i < kSets; ++i) {
+        e = hipEventCreateWithFlags(&x->ev_front[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_scan[i], hipEventDisableTiming);
+        if (e == hipSuccess && i > 0) e = hipEventCreateWithFlags(&x->sc[i].end, hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&x->h_counters), sizeof(unsigned long long) * kNumCounters);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_search_end, hipEventDisableTiming);
+    x->sc[0].end = x->ev_search_end;
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_probes, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_done, hipEventDisableTiming);
     for (int i = 0; e == hipSuccess && i < kMaxStage; ++i) {
-        e = hipEventCreateWithFlags(&x->stage_ready[i], hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&x->stage_free[i], hipEventDisableTiming);
+        e = hipEventCreateWithFlags(&x->stage_free[i], hipEventDisableTiming);
+        for (int sd = 0; e == hipSuccess && sd < kMaxSide; ++sd)
+            e = hipEventCreateWithFlags(&x->stage_ready[i][sd], hipEventDisableTiming);
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -345,16 +661,27 @@ void ivf_index_destroy(ivf_index* x) {
     if (!x) return;
     (void)hipDeviceSynchronize();
     free_index_data(x);
+    dfree(x->d_codebooks);
     for (int i = 0; i < kMaxSide; ++i)
         if (x->side[i]) (void)hipStreamDestroy(x->side[i]);
     if (x->move_stream) (void)hipStreamDestroy(x->move_stream);
     if (x->patch_stream) (void)hipStreamDestroy(x->patch_stream);
+    if (x->pipe_scan) (void)hipStreamDestroy(x->pipe_scan);
+    for (int i = 0; i < 2; ++i)
+        if (x->pipe_front[i]) (void)hipStreamDestroy(x->pipe_front[i]);
+    for (int i = 0; i < kSets; ++i) {
+        if (x->ev_front[i]) (void)hipEventDestroy(x->ev_front[i]);
+        if (x->ev_scan[i]) (void)hipEventDestroy(x->ev_scan[i]);
+        if (i > 0 && x->sc[i].end) (void)hipEventDestroy(x->sc[i].end);
+    }
+    if (x->h_counters) (void)hipHostFree(x->h_counters);
     if (x->ev_search_end) (void)hipEventDestroy(x->ev_search_end);
     for (hipEvent_t e : x->spare_events) (void)hipEventDestroy(e);
     if (x->ev_probes) (void)hipEventDestroy(x->ev_probes);
     if (x->ev_done) (void)hipEventDestroy(x->ev_done);
     for (int i = 0; i < kMaxStage; ++i) {
-        if (x->stage_ready[i]) (void)hipEventDestroy(x->stage_ready[i]);
+        for (int sd = 0; sd < kMaxSide; ++sd)
+            if (x->stage_ready[i][sd]) (void)hipEventDestroy(x->stage_ready[i][sd]);
         if (x->stage_free[i]) (void)hipEventDestroy(x->stage_free[i]);
     }
     for (int sl = 0; sl < kTimingSlots; ++sl)
@@ -363,12 +690,38 @@ void ivf_index_destroy(ivf_index* x) {
     delete x;
 }
 
+int ivf_index_set_pq_codebooks(ivf_index* x, int d, int m, const float* codebooks) {
+    if (!x || !codebooks) return fail(IVF_ERR_INVALID, "index or codebooks is NULL");
+    if (x->uploading) return fail(IVF_ERR_INVALID, "codebooks cannot change during an upload");
+    if (d <= 0 || m <= 0 || d % m != 0) return fail(IVF_ERR_INVALID, "d must be a positive multiple of m");
+    if (m % 16 != 0 || m > kPqMaxM) return fail(IVF_ERR_LIMIT, "m must be a multiple of 16 and at most %d (got %d)", kPqMaxM, m);
+    if (x->ready && x->dtype == IVF_PQ8) return fail(IVF_ERR_INVALID, "the index holds codes of the current codebooks: upload anew first");
+    (void)hipDeviceSynchronize();
+    dfree(x->d_codebooks);
+    x->pq_m = x->pq_d = 0;
+    size_t tot = 0;
+    int rc;
+    if ((rc = dalloc(x->d_codebooks, (size_t)256 * d, tot))) return rc;
+    HIP_TRY(hipMemcpy(x->d_codebooks, codebooks, sizeof(float) * 256 * (size_t)d, hipMemcpyDefault));
+    if (!x->pq_lds_set) {
+        // a table of up to 128 KiB in LDS is beyond the default allowance of a workgroup
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_pq_scan), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kPqMaxM * 1024));
+        x->pq_lds_set = true;
+    }
+    x->pq_m = m;
+    x->pq_d = d;
+    return 0;
+}
+
 int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const float* centroids,
                            int dtype, const int64_t* list_offsets) {
     if (!x) return fail(IVF_ERR_INVALID, "index is NULL");
     if (!centroids || !list_offsets) return fail(IVF_ERR_INVALID, "centroids or list_offsets is NULL");
-    if (dtype != IVF_FP32 && dtype != IVF_FP16 && dtype != IVF_INT8)
-        return fail(IVF_ERR_INVALID, "dtype must be IVF_FP32, IVF_FP16 or IVF_INT8");
+    if (dtype != IVF_FP32 && dtype != IVF_FP16 && dtype != IVF_INT8 && dtype != IVF_PQ8)
+        return fail(IVF_ERR_INVALID, "dtype must be IVF_FP32, IVF_FP16, IVF_INT8 or IVF_PQ8");
+    if (dtype == IVF_PQ8 && (!x->d_codebooks || x->pq_d != d))
+        return fail(IVF_ERR_INVALID, "IVF_PQ8 needs codebooks for this dimension first (ivf_index_set_pq_codebooks)");
     if (d <= 0 || nlist <= 0 || n < 0) return fail(IVF_ERR_INVALID, "d, nlist must be positive and n non-negative");
     if (d % 8 != 0 || d > 4096) return fail(IVF_ERR_LIMIT, "d must be a multiple of 8 and at most 4096 (got %d)", d);
     if (dtype == IVF_INT8 && d % 16 != 0) return fail(IVF_ERR_LIMIT, "d must be a multiple of 16 for int8 storage (got %d)", d);
@@ -376,10 +729,10 @@ int ivf_index_upload_begin(ivf_index* x, int d, int64_t nlist, int64_t n, const 
         return fail(IVF_ERR_LIMIT, "n must be below 2^32 and nlist below 2^28");
     (void)hipDeviceSynchronize();
     free_index_data(x);
-    x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : dtype == IVF_INT8 ? 1 : 4;
+    x->d = d; x->dtype = dtype; x->es = dtype == IVF_FP16 ? 2 : (dtype == IVF_INT8 || dtype == IVF_PQ8) ? 1 : 4;
     x->nlist = nlist; x->n = n;
     x->tail_bytes = dtype == IVF_INT8 ? 4 : 0;       // int8 records end with their fp32 scale
-    x->row_bytes = (size_t)d * x->es + x->tail_bytes;
+    x->row_bytes = dtype == IVF_PQ8 ? (size_t)x->pq_m : (size_t)d * x->es + x->tail_bytes;
     x->block_bytes = x->row_bytes * kLanes;
     try {
         x->offsets.assign((size_t)nlist + 1, 0);
@@ -647,151 +1000,97 @@ int ivf_budget_wait(ivf_index* x) {
 
 int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
                float* out_scores, void* stream) {
-    int rc = check_ready(x);
-    if (rc) return rc;
-    if (nq < 0) return fail(IVF_ERR_INVALID, "nq must be non-negative");
-    if (nq == 0) return 0;
-    if (!queries || !out_ids || !out_scores) return fail(IVF_ERR_INVALID, "queries, out_ids or out_scores is NULL");
-    if (nprobe <= 0 || k <= 0) return fail(IVF_ERR_INVALID, "nprobe and k must be positive");
-    if (k > kMaxK) return fail(IVF_ERR_LIMIT, "k above %d", kMaxK);
-    if (nprobe > x->nlist) nprobe = (int)x->nlist;
-    if (nprobe > kMaxK) return fail(IVF_ERR_LIMIT, "nprobe above %d", kMaxK);
-    if (nq > 65535) return fail(IVF_ERR_LIMIT, "nq above 65535");
-    if ((uint64_t)nq * (uint64_t)nprobe >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "nq*nprobe above 2^31");
-    if ((uint64_t)block_bound(x, nq, nprobe) >= (1ull << 31)) return fail(IVF_ERR_LIMIT, "batch too large for one call");
-    {
-        int dev = -1;
-        if (hipGetDevice(&dev) != hipSuccess || dev != x->device)
-            return fail(IVF_ERR_INVALID, "the index lives on HIP device %d but the current device is %d", x->device, dev);
-    }
+    SearchCtx c;
+    int rc = search_args(x, queries, nq, nprobe, k, out_ids, out_scores, c);
+    if (rc) return rc < 0 ? rc : 0;          // 1: nothing to do
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool moving = moves_active(x);
-    if (moving) {
-        // a budget change is under way: take over what has landed, issue more copies, and
-        // let this search start only behind the latest update of the address table
-        if ((rc = moves_advance(x))) return rc;
-        if (!x->limbo.empty()) HIP_TRY(hipStreamWaitEvent(st, x->limbo.back().after, 0));
-    }
-    const bool offload = x->resident_lists < x->nlist && !x->opt_host_direct;
-    if (offload && (rc = ensure_staging(x))) return rc;
-    if ((rc = ensure_scratch(x, nq, nprobe, offload))) {
+    Scratch& s = x->sc[0];
+    if ((rc = order_after_last_use(s, st, st))) return rc;
+    if ((rc = search_prologue(x, st, c))) return rc;
+    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload))) {
         // a failed growth leaves some buffers freed: drop all of them so that the sizes on
         // record match what exists (the next search allocates afresh); the error message stays
         std::string msg = g_err;
         (void)hipDeviceSynchronize();
-        free_scratch(x->sc);
+        free_scratch(s);
         g_err = msg;
         return rc;
     }
-    Scratch& s = x->sc;
-    const int nlist = (int)x->nlist;
-    const int ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
-    const int npairs = (int)(nq * nprobe);
-    // Running lower bound of each query's k-th best score, kept by the scan so that it
-    // can skip storing blocks that cannot matter: from one block's k-th largest value
-    // (k <= 64) or from the two best blocks' ceil(k/2)-th largest (k <= 128).
-    // Small plans run as one wave of work items, where nothing has a bound to prune by yet.
-    const bool small_plan = x->opt_scan_prune != 2 && block_bound(x, nq, nprobe) < 32768;
-    if (!x->opt_scan_prune || k > 128 || small_plan) { x->prune_blocks = 0; x->prune_j = 0; }
-    else if (k <= 64) { x->prune_blocks = 1; x->prune_j = k; }
-    else { x->prune_blocks = 2; x->prune_j = (k + 1) / 2; }
-    const int tm = x->timing;                  // 0 off, 1 every stage, 2 the scan and streaming stages only
-    hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
-    int evi = 0;
-    auto mark = [&]() {
-        if (tm == 1 || (tm == 2 && evi >= 3 && evi <= 5)) (void)hipEventRecord(evs[evi], st);
-        ++evi;
-    };
+    return search_serial(x, s, c, st);
+}
 
-    mark();   // 0
-    const int nz = (int)(2 * (size_t)nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq);   // cleared by the coarse kernel
-    {
-        // Query rows per wavefront: as many as possible (each centroid row is then fetched
-        // once), but few enough that the grid still offers every SIMD a wavefront.
-        dim3 grid((unsigned)((nlist + kCoarseNT - 1) / kCoarseNT), 1);
-        const int64_t simds = (int64_t)x->cus * 4, waves_x = (int64_t)grid.x * 4;
-        int mt = nq > 64 ? 4 : nq > 32 ? 2 : 1;
-        while (mt > 1 && waves_x * ((nq + 32 * mt - 1) / (32 * mt)) < simds) mt >>= 1;
-        grid.y = (unsigned)((nq + 32 * mt - 1) / (32 * mt));
-        if (mt == 1)
-            hipLaunchKernelGGL((k_coarse<1>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
-        else if (mt == 2)
-            hipLaunchKernelGGL((k_coarse<2>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
-        else
-            hipLaunchKernelGGL((k_coarse<4>), grid, dim3(256), 0, st, queries, x->d_centroids, s.S, s.tmax, (int)nq, nlist, x->d, ntile, s.zeroed, nz);
+int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
+                      float* out_scores, void* stream, void* queries_ready) {
+    SearchCtx c;
+    int rc = search_args(x, queries, nq, nprobe, k, out_ids, out_scores, c);
+    if (rc) return rc < 0 ? rc : 0;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t ready = static_cast<hipEvent_t>(queries_ready);
+    // Budget changes under way, the staged host-list mode and per-stage timing keep a search
+    // on one stream; it then starts behind the queries like any other work of that stream.
+    // So does a search whose scan is bounded by a few tens of microseconds: the overlap
+    // cannot repay the dozen extra stream and event calls it takes.
+    const uint64_t bound_bytes = (uint64_t)block_bound(x, c.nq, c.nprobe) * x->block_bytes;
+    const bool tiny = bound_bytes < ((uint64_t)x->opt_queue_min_mb << 20);
+    const bool serial = tiny || stream_is_capturing(st) || moves_active(x) || (x->resident_lists < x->nlist && !x->opt_host_direct) || x->timing == 1;
+    const int p = serial ? 0 : x->next_set;
+    // Under a scan the front kernels (chains of dependent loads) run several times slower
+    // than alone.  Behind a short scan (a few hundred microseconds) one search's worth of
+    // them no longer fits, and the searches' front stages alternate between two streams;
+    // behind a long scan a second stream only takes more from the scan.
+    const int fronts = x->opt_queue_fronts ? (int)x->opt_queue_fronts : bound_bytes < ((uint64_t)4 << 30) ? 2 : 1;
+    hipStream_t first = serial ? st : x->pipe_front[x->queued_count % (uint64_t)fronts];
+    Scratch& s = x->sc[p];
+    if ((rc = order_after_last_use(s, st, first))) return rc;
+    if (serial) {
+        if (ready) HIP_TRY(hipStreamWaitEvent(st, ready, 0));
+        if ((rc = search_prologue(x, st, c))) return rc;
     }
-    mark();   // 1
-    int* hist = s.zeroed;
-    int* cursor = s.zeroed + nlist;
-    // The selection kernels are chains of barriers and dependent loads: with little to select
-    // from, a workgroup of 4 wavefronts gets through them faster than one of 16.
-    const bool small_probe = x->opt_sel_threads ? x->opt_sel_threads == 256 : ntile <= 128;
-    const bool small_final = x->opt_sel_threads ? x->opt_sel_threads == 256 : block_bound(x, 1, nprobe) <= 128;
-    if (small_probe)
-        hipLaunchKernelGGL((k_probe_select<256>), dim3((unsigned)nq), dim3(256), 0, st, s.S, s.tmax, nlist, ntile, nprobe,
-                           s.probes, hist);
-    else
-        hipLaunchKernelGGL((k_probe_select<kSelThreads>), dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.S, s.tmax, nlist,
-                           ntile, nprobe, s.probes, hist);
-    mark();   // 2
-    if (offload) {
-        HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)npairs, hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipEventRecord(x->ev_probes, st));
+    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload))) {
+        std::string msg = g_err;
+        (void)hipDeviceSynchronize();
+        free_scratch(s);
+        g_err = msg;
+        return rc;
     }
-    if (x->opt_regroup_fused && nlist <= kFusedMaxLists && npairs <= kFusedMaxPairs) {
-        // few lists and pairs: one workgroup does the whole regrouping in one launch
-        hipLaunchKernelGGL(k_regroup_small, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
-                           nlist, nprobe, x->block_bytes, s.probes, npairs, cursor, s.pair_start, s.sblk_start,
-                           s.item_start, s.pair_flat, s.pair_of_probe, s.items, x->d_hits, s.counters);
-    } else {
-        const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
-        hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
-                           nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
-        hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, hist, nlist, (int)wgs, s.wg_totals,
-                           s.pair_start, s.sblk_start, s.item_start);
-        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
-                           s.pair_start, cursor, s.pair_flat);
-        hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
-                           x->d_list_ptr, nlist, nprobe, x->block_bytes, s.pair_start, s.sblk_start, s.item_start,
-                           s.pair_flat, s.pair_of_probe, s.items, x->d_hits);
-    }
-    mark();   // 3
-    if (x->resident_lists > 0 || x->opt_host_direct) {
-        const int mode = (int)x->opt_scan_mode;
-        const int64_t bound = std::max<int64_t>(1, block_bound(x, nq, nprobe));
-        launch_scan(x, (size_t)bound, st, s.items, s.counters + kCntItems, 0, queries, mode);
-    }
-    mark();   // 4
+    if (serial) return search_serial(x, s, c, st);
+
+    // By stage: the front stages of consecutive searches alternate between two streams of
+    // the library, every scan runs on a third behind the scan of the search before, and the
+    // final selection runs on the caller's stream, where the results are wanted (four
+    // streams in all: a process has four hardware queues, and streams that share one run
+    // one after the other).  Events carry a search from stage to stage and hand its scratch
+    // set (one of kSets, taken in turn) to the search that uses it next.
+    hipStream_t front = first, scan = x->pipe_scan;
+    x->queued_count += 1;
+    const int tm = x->timing;                  // 0 or 2 here
+    hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
+    search_set_pruning(x, c);
+    if (ready) HIP_TRY(hipStreamWaitEvent(front, ready, 0));
+    enqueue_coarse(x, s, c, front);
+    enqueue_probe_select(x, s, c, front);
+    enqueue_regroup(x, s, c, front, true);
     HIP_TRY(hipGetLastError());
-    if (offload) {
-        if ((rc = stream_host_lists(x, queries, nq, nprobe, st))) return rc;
-    }
-    mark();   // 5
-    ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
-    if (small_final)
-        hipLaunchKernelGGL((k_final_select<256>), dim3((unsigned)nq), dim3(256), 0, st, s.probes, s.pair_of_probe,
-                           s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos, x->d_id_sorted, nprobe, k,
-                           x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
-    else
-        hipLaunchKernelGGL((k_final_select<kSelThreads>), dim3((unsigned)nq), dim3(kSelThreads), 0, st, s.probes,
-                           s.pair_of_probe, s.pair_start, s.sblk_start, lt, s.bmax, s.scores, x->d_rank_of_pos,
-                           x->d_id_sorted, nprobe, k, x->prune_blocks ? s.qthr : nullptr, out_ids, out_scores);
-    mark();   // 6
+    HIP_TRY(hipEventRecord(x->ev_front[p], front));
+    HIP_TRY(hipStreamWaitEvent(scan, x->ev_front[p], 0));
+    // with timing on, the event behind the scan also tells the final selection to start:
+    // every record on the scan's stream is a gap between two scans
+    hipEvent_t scan_done = tm ? evs[4] : x->ev_scan[p];
+    c.scan_start = tm ? evs[3] : nullptr;
+    c.scan_stop = scan_done;
+    enqueue_scan(x, s, c, scan);
     HIP_TRY(hipGetLastError());
-    if (offload) {
-        HIP_TRY(hipEventRecord(x->ev_done, st));
-        x->done_recorded = true;
+    HIP_TRY(hipStreamWaitEvent(st, scan_done, 0));
+    enqueue_final_select(x, s, c, st);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s.end, st));
+    s.end_recorded = true;
+    x->next_set = (p + 1) % kSets;
+    search_epilogue(x, s, c, st, true);
+    if (tm) {
+        x->ev_queued[x->timed_searches % kTimingSlots] = true;
+        x->timed_searches += 1;
     }
-    if (moving || moves_active(x)) {
-        // old places of moved lists are released only behind the searches that may read them
-        HIP_TRY(hipEventRecord(x->ev_search_end, st));
-        x->search_end_recorded = true;
-    }
-    x->last_nq = (int)nq;
-    x->last_nprobe = nprobe;
-    x->last_stream = st;
-    x->last_offload = offload;
-    if (tm) x->timed_searches += 1;
     return 0;
 }
 
@@ -808,7 +1107,8 @@ int ivf_get_info(ivf_index* x, ivf_info* out) {
     out->device_list_bytes = dev;
     out->host_list_bytes = out->index_bytes - dev;
     out->resident_lists = x->resident_lists;
-    out->scratch_bytes = (int64_t)x->sc.bytes;
+    out->scratch_bytes = 0;
+    for (int p = 0; p < kSets; ++p) out->scratch_bytes += (int64_t)x->sc[p].bytes;
     out->device_pool_bytes = (int64_t)(x->dpool.allocated_blocks() * x->block_bytes);
     out->host_pool_bytes = (int64_t)(x->hpool.allocated_blocks() * x->block_bytes);
     out->moved_h2d_bytes = x->moved_h2d;
@@ -820,8 +1120,8 @@ int ivf_get_info(ivf_index* x, ivf_info* out) {
 int ivf_debug_last_probes(ivf_index* x, int32_t* out_lists, void* stream) {
     int rc = check_ready(x);
     if (rc) return rc;
-    if (!out_lists || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out_lists is NULL");
-    HIP_TRY(hipMemcpyAsync(out_lists, x->sc.probes, sizeof(int32_t) * (size_t)x->last_nq * x->last_nprobe,
+    if (!out_lists || x->last_nq == 0 || !x->last_sc) return fail(IVF_ERR_INVALID, "no search yet or out_lists is NULL");
+    HIP_TRY(hipMemcpyAsync(out_lists, x->last_sc->probes, sizeof(int32_t) * (size_t)x->last_nq * x->last_nprobe,
                            hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
     return 0;
 }
@@ -829,8 +1129,8 @@ int ivf_debug_last_probes(ivf_index* x, int32_t* out_lists, void* stream) {
 int ivf_debug_last_coarse(ivf_index* x, float* out_scores, void* stream) {
     int rc = check_ready(x);
     if (rc) return rc;
-    if (!out_scores || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out_scores is NULL");
-    HIP_TRY(hipMemcpyAsync(out_scores, x->sc.S, sizeof(float) * (size_t)x->last_nq * (size_t)x->nlist,
+    if (!out_scores || x->last_nq == 0 || !x->last_sc) return fail(IVF_ERR_INVALID, "no search yet or out_scores is NULL");
+    HIP_TRY(hipMemcpyAsync(out_scores, x->last_sc->S, sizeof(float) * (size_t)x->last_nq * (size_t)x->nlist,
                            hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
     return 0;
 }
@@ -887,19 +1187,20 @@ int ivf_debug_read_list(ivf_index* x, int64_t list, void* out_vectors, int64_t* 
 int ivf_last_search_stats(ivf_index* x, ivf_search_stats* out) {
     int rc = check_ready(x);
     if (rc) return rc;
-    if (!out || x->last_nq == 0) return fail(IVF_ERR_INVALID, "no search yet or out is NULL");
-    HIP_TRY(hipStreamSynchronize(x->last_stream));
+    if (!out || x->last_nq == 0 || !x->last_sc) return fail(IVF_ERR_INVALID, "no search yet or out is NULL");
+    if (x->last_sc->end_recorded) HIP_TRY(hipEventSynchronize(x->last_sc->end));
+    else HIP_TRY(hipDeviceSynchronize());           // the search was captured into a graph: no event of its own
     if (!x->last_offload) {
-        Scratch& s = x->sc;
-        HIP_TRY(hipMemcpy(s.h_counters, s.counters, sizeof(unsigned long long) * kNumCounters, hipMemcpyDeviceToHost));
+        const unsigned long long* hc = x->h_counters;
+        HIP_TRY(hipMemcpy(x->h_counters, x->last_sc->counters, sizeof(unsigned long long) * kNumCounters, hipMemcpyDeviceToHost));
         ivf_search_stats t = {};
-        t.pairs = (int64_t)s.h_counters[kCntPairs];
-        t.unique_lists = (int64_t)s.h_counters[kCntUnique];
-        t.scanned_vectors = (int64_t)s.h_counters[kCntVectors];
+        t.pairs = (int64_t)hc[kCntPairs];
+        t.unique_lists = (int64_t)hc[kCntUnique];
+        t.scanned_vectors = (int64_t)hc[kCntVectors];
         t.scan_bytes = t.scanned_vectors * (int64_t)x->row_bytes;
-        t.scan_bytes_resident = (int64_t)s.h_counters[kCntVectorsResident] * (int64_t)x->row_bytes;
+        t.scan_bytes_resident = (int64_t)hc[kCntVectorsResident] * (int64_t)x->row_bytes;
         t.scan_bytes_streamed = t.scan_bytes - t.scan_bytes_resident;
-        t.scan_items = (int64_t)s.h_counters[kCntItems];
+        t.scan_items = (int64_t)hc[kCntItems];
         x->last_stats = t;
     }
     *out = x->last_stats;
@@ -925,8 +1226,15 @@ int ivf_get_stage_ms(ivf_index* x, int back, float* ms) {
     if (!ms) return fail(IVF_ERR_INVALID, "ms is NULL");
     if (back < 0 || back >= kTimingSlots || back >= x->timed_searches)
         return fail(IVF_ERR_INVALID, "no timed search %d calls back (kept: %d)", back, kTimingSlots);
-    hipEvent_t* evs = x->ev[(x->timed_searches - 1 - back) % kTimingSlots];
+    const int slot = (int)((x->timed_searches - 1 - back) % kTimingSlots);
+    hipEvent_t* evs = x->ev[slot];
     for (int i = 0; i < IVF_NUM_STAGES; ++i) ms[i] = 0.f;
+    if (x->ev_queued[slot]) {                // a queued search: events around its scan only
+        HIP_TRY(hipEventSynchronize(evs[4]));
+        HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_SCAN], evs[3], evs[4]));
+        ms[IVF_STAGE_TOTAL] = ms[IVF_STAGE_SCAN];
+        return 0;
+    }
     if (x->timing == 2) {                    // only the scan and streaming stages were recorded
         HIP_TRY(hipEventSynchronize(evs[5]));
         HIP_TRY(hipEventElapsedTime(&ms[IVF_STAGE_SCAN], evs[3], evs[4]));
@@ -965,10 +1273,11 @@ int ivf_debug_read(const void* src, int64_t bytes, void* sink, void* stream) {
 int ivf_set_option(ivf_index* x, const char* name, int64_t value) {
     if (!x || !name) return fail(IVF_ERR_INVALID, "index or name is NULL");
     std::string n(name);
-    if (n == "scan_mode" && (value == 0 || value == 1)) x->opt_scan_mode = value;
-    else if (n == "scan_unroll" && (value == 8 || value == 16)) x->opt_scan_unroll = value;
+    if (n == "scan_unroll" && (value == 8 || value == 16)) x->opt_scan_unroll = value;
+    else if (n == "queue_fronts" && value >= 0 && value <= 2) x->opt_queue_fronts = value;   // 0: by the size of the scan
+    else if (n == "queue_min_mb" && value >= 0 && value <= (1 << 20)) x->opt_queue_min_mb = value;
+    else if (n == "scan_split" && (value == 0 || value == 1 || value == 2 || value == 4)) x->opt_scan_split = value;   // 0: by block size
     else if (n == "scan_waves" && (value == 1 || value == 2 || value == 4 || value == 8)) x->opt_scan_waves = value;
-    else if (n == "scan_wgs_per_cu" && value >= 1 && value <= 16) x->opt_scan_wgs_per_cu = value;
     else if (n == "scan_prune" && value >= 0 && value <= 2) x->opt_scan_prune = value;   // 2 = also on small plans
     else if (n == "host_direct" && (value == 0 || value == 1)) {
         // 1: the scan kernel reads host-resident lists straight from pinned host memory

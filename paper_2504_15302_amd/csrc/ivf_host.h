@@ -2,6 +2,7 @@
 // index object behind the opaque handle of include/ivf.h.  Included by ivf_api.hip only.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cstdarg>
@@ -19,6 +20,7 @@
 #include "ivf_coarse.h"
 #include "ivf_device.h"
 #include "ivf_pool.h"
+#include "ivf_pq.h"
 #include "ivf_regroup.h"
 #include "ivf_scan.h"
 #include "ivf_select.h"
@@ -103,15 +105,22 @@ struct Scratch {
     ScanItem* stream_items = nullptr;
     float* scores = nullptr;
     float* bmax = nullptr;
+    float* pq_tables = nullptr;     // product-quantised lists: [nq][M][256] inner products with the codewords
+    size_t cap_pq_q = 0;
     // pinned host mirrors for the streamed path
     int32_t* h_probes = nullptr;
     size_t h_probes_cap = 0;
     ScanItem* h_items = nullptr;
     size_t h_items_cap = 0;
-    unsigned long long* h_counters = nullptr;
     size_t bytes = 0;
+    // Recorded behind the last kernel of the last search that used this set, on whatever
+    // stream that was: the next search that uses the set starts behind it.  The handle
+    // belongs to the index and outlives the buffers.
+    hipEvent_t end = nullptr;
+    bool end_recorded = false;
 };
 
+constexpr int kSets = 3;           // scratch sets that queued searches go round
 constexpr int kMaxStage = 8;
 constexpr int kMaxSide = 4;
 constexpr int kTimingSlots = 64;   // searches whose stage events are kept
@@ -146,6 +155,9 @@ struct ivf_index {
     int cus = 256;
     bool uploading = false, ready = false;
     int d = 0, dtype = 0, es = 4;
+    int pq_m = 0, pq_d = 0;                     // codebooks on record (ivf_index_set_pq_codebooks)
+    float* d_codebooks = nullptr;               // [pq_m][256][pq_d / pq_m]
+    bool pq_lds_set = false;                    // the code scan has been allowed its dynamic LDS
     int64_t nlist = 0, n = 0, next_list = 0;
     size_t row_bytes = 0, block_bytes = 0;      // one stored vector as uploaded; 64 of them, blocked
     int tail_bytes = 0;                         // bytes of a row behind its d elements (int8: the scale)
@@ -181,7 +193,7 @@ struct ivf_index {
     int move_rc = 0;                   // why the last change stopped early (0: it did not)
     std::string move_msg;
     hipStream_t move_stream = nullptr, patch_stream = nullptr;
-    hipEvent_t ev_search_end = nullptr;
+    hipEvent_t ev_search_end = nullptr;   // = sc[0].end: searches on one stream (the only kind while lists move) use set 0
     bool search_end_recorded = false;
     std::vector<hipEvent_t> spare_events;
     std::vector<const void**> spare_tables;
@@ -189,25 +201,37 @@ struct ivf_index {
     // streaming of host-resident lists
     hipStream_t side[kMaxSide] = {};   // copy streams for host-resident lists (chunks alternate)
     char* stage[kMaxStage] = {};
-    hipEvent_t stage_ready[kMaxStage] = {}, stage_free[kMaxStage] = {};
+    hipEvent_t stage_ready[kMaxStage][kMaxSide] = {}, stage_free[kMaxStage] = {};
     bool stage_used[kMaxStage] = {};
     size_t stage_bytes = 0;
     int nstage = 0;
     hipEvent_t ev_probes = nullptr, ev_done = nullptr;
     bool done_recorded = false;
     // search state
-    Scratch sc;
+    Scratch sc[kSets];                 // queued searches go round the sets; searches on one stream use set 0
+    Scratch* last_sc = nullptr;        // set of the last search (introspection calls read it)
+    unsigned long long* h_counters = nullptr;   // pinned landing place of a set's counters
     int prune_blocks = 0, prune_j = 0;   // bound kept by the scan for the current search (see k_scan)
     int last_nq = 0, last_nprobe = 0;
     hipStream_t last_stream = nullptr;
     bool last_offload = false;
+    // queued searches (ivf_search_queued): a search's front stages run on one of two
+    // front streams (taken in turn: under a scan these latency-bound kernels run several
+    // times slower than alone, and two searches' worth side by side keep up with the scans),
+    // its scan on pipe_scan behind the scan before it, its final selection on the caller's stream
+    hipStream_t pipe_front[2] = {}, pipe_scan = nullptr;
+    uint64_t queued_count = 0;
+    hipEvent_t ev_front[kSets] = {}, ev_scan[kSets] = {};
+    int next_set = 0;
+    bool last_queued = false;
     ivf_search_stats last_stats = {};
     int timing = 0;                    // 0 off, 1 every stage, 2 scan and streaming stages only
     hipEvent_t ev[kTimingSlots][kEvPerSearch] = {};
     bool ev_created = false;
+    bool ev_queued[kTimingSlots] = {};  // the slot's search was a queued one: only its scan was timed
     int64_t timed_searches = 0;        // searches recorded since timing was switched on
     // options
-    int64_t opt_scan_mode = 0, opt_scan_unroll = 16, opt_scan_wgs_per_cu = 2, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 1, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
+    int64_t opt_queue_min_mb = 256, opt_queue_fronts = 0, opt_scan_split = 0, opt_scan_unroll = 16, opt_scan_waves = 4, opt_scan_prune = 1, opt_host_direct = 1, opt_nside = 4, opt_policy = 0, opt_segment_mb = 2048, opt_stage_mb = 64,
             opt_nstage = 3, opt_move_chunk_kb = 64 << 10, opt_move_inflight_kb = 4 << 20, opt_sel_threads = 0, opt_regroup_fused = 1;
 };
 

@@ -37,8 +37,7 @@ int upload_list_ptr_table(ivf_index* x) {
     return 0;
 }
 
-// Upper bound on score blocks (and scan items) of a batch: every query probing the
-// nprobe longest lists.
+// Events and pinned table snapshots are recycled between budget changes.
 hipEvent_t take_event(ivf_index* x) {
     if (!x->spare_events.empty()) {
         hipEvent_t e = x->spare_events.back();

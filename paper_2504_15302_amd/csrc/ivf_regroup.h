@@ -168,7 +168,7 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
     if (l >= nlist) return;
     const unsigned cnt = (unsigned)hist[l] & kHistCountMask;
     if (!cnt) return;
-    hits[l] += cnt;                  // lifetime probe count of the list (residency policy)
+    atomicAdd(&hits[l], cnt);        // lifetime probe count of the list (residency policy); queued searches may regroup side by side
     const uint32_t ps = pair_start[l];
     uint32_t* seg = pair_flat + ps;
     for (unsigned i = 1; i < cnt; ++i) {        // insertion sort: segments are tiny
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kScanThreads) void k_regroup_small(
         const unsigned h = (unsigned)hist[l];
         const unsigned cnt = h & kHistCountMask;
         if (!cnt) continue;
-        hits[l] += cnt;
+        atomicAdd(&hits[l], cnt);
         const uint32_t ps = pair_start[l];
         uint32_t* seg = pair_flat + ps;
         for (unsigned i = 1; i < cnt; ++i) {

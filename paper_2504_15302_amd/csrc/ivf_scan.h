@@ -125,17 +125,14 @@ __device__ __forceinline__ void fma_group(const ScanBuf<NQ, UU, E>& b, float (&a
     }
 }
 
+// Inner products of the lane's vector with the NQ queries of the item over the 16-byte
+// chunks [c0, c1) of the vector: acc[g] = sum in ascending chunk order, starting from 0.
 template <int ST, int NQ, int U>
-__device__ __forceinline__ void scan_item(const ScanItem& it, const float* __restrict__ Q,
-                                          int d, float* __restrict__ scores,
-                                          float* __restrict__ bmax, int lane,
-                                          unsigned long long* __restrict__ qthr, int prune_blocks,
-                                          int prune_j) {
+__device__ __forceinline__ void scan_accumulate(const ScanItem& it, const float* __restrict__ Q, int d,
+                                                int c0, int c1, int lane, float (&acc)[kQB]) {
     constexpr int E = Store<ST>::E;
-    const int nchunk = d / E;
-    const int nq = (int)it.nq;
     // lanes past the end of the list re-read the last valid vector (same cache lines,
-    // no extra traffic, no divergence); their results are discarded below
+    // no extra traffic, no divergence); their results are discarded later
     const int ld_lane = min(lane, (int)it.nvalid - 1);
     const gptr_u4 src = (gptr_u4)(uintptr_t)it.data + ld_lane;
 
@@ -144,39 +141,53 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
     for (int g = 0; g < NQ; ++g) {
         qrow[g] = Q + (size_t)it.q[g] * d;
     }
-    float acc[NQ];
+    float a[NQ];
 #pragma unroll
-    for (int g = 0; g < NQ; ++g) acc[g] = 0.f;
-    float scale = 1.f;                              // int8: the lane's scale sits behind the codes
-    if constexpr (ST == kI8)
-        scale = *(reinterpret_cast<const float*>(static_cast<const char*>(it.data) + (size_t)nchunk * kLanes * 16) + ld_lane);
+    for (int g = 0; g < NQ; ++g) a[g] = 0.f;
 
     // two register buffers: the loads of group i+1 are in flight while group i is used
     ScanBuf<NQ, U, E> bufA, bufB;
-    const int ngroup = nchunk / U;
+    const int ngroup = (c1 - c0) / U;
     if (ngroup > 0) {
         int gi = 0;
-        load_group(bufA, src, 0, qrow, lane);
+        load_group(bufA, src, c0, qrow, lane);
         for (; gi + 2 < ngroup; gi += 2) {           // bufA holds group gi
-            load_group(bufB, src, (gi + 1) * U, qrow, lane);
-            fma_group<ST>(bufA, acc);
-            load_group(bufA, src, (gi + 2) * U, qrow, lane);
-            fma_group<ST>(bufB, acc);
+            load_group(bufB, src, c0 + (gi + 1) * U, qrow, lane);
+            fma_group<ST>(bufA, a);
+            load_group(bufA, src, c0 + (gi + 2) * U, qrow, lane);
+            fma_group<ST>(bufB, a);
         }
         if (gi + 1 < ngroup) {
-            load_group(bufB, src, (gi + 1) * U, qrow, lane);
-            fma_group<ST>(bufA, acc);
-            fma_group<ST>(bufB, acc);
+            load_group(bufB, src, c0 + (gi + 1) * U, qrow, lane);
+            fma_group<ST>(bufA, a);
+            fma_group<ST>(bufB, a);
         } else {
-            fma_group<ST>(bufA, acc);
+            fma_group<ST>(bufA, a);
         }
     }
-    for (int c = ngroup * U; c < nchunk; ++c) {     // d not a multiple of the group width
+    for (int c = c0 + ngroup * U; c < c1; ++c) {    // the range is not a multiple of the group width
         ScanBuf<NQ, 1, E> one;
         load_group(one, src, c, qrow, lane);
-        fma_group<ST>(one, acc);
+        fma_group<ST>(one, a);
     }
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) acc[g] = a[g];
+}
 
+// What happens to the 64 x NQ sums of an item: block maxima always, the scores themselves
+// unless the running bound of the query says that nothing here can enter its top-k.
+template <int ST, int NQ>
+__device__ __forceinline__ void scan_finish(const ScanItem& it, int d, const float (&acc)[kQB],
+                                            float* __restrict__ scores, float* __restrict__ bmax, int lane,
+                                            unsigned long long* __restrict__ qthr, int prune_blocks,
+                                            int prune_j) {
+    constexpr int E = Store<ST>::E;
+    const int nchunk = d / E;
+    const int nq = (int)it.nq;
+    const int ld_lane = min(lane, (int)it.nvalid - 1);
+    float scale = 1.f;                              // int8: the lane's scale sits behind the codes
+    if constexpr (ST == kI8)
+        scale = *(reinterpret_cast<const float*>(static_cast<const char*>(it.data) + (size_t)nchunk * kLanes * 16) + ld_lane);
     const bool valid = lane < (int)it.nvalid;
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
@@ -227,52 +238,91 @@ __device__ __forceinline__ void scan_item(const ScanItem& it, const float* __res
 }
 
 template <int ST, int U>
+__device__ __forceinline__ void accumulate_dispatch(const ScanItem& it, const float* __restrict__ Q, int d,
+                                                    int c0, int c1, int lane, float (&acc)[kQB]) {
+    if (it.nq == 1) scan_accumulate<ST, 1, U>(it, Q, d, c0, c1, lane, acc);
+    else if (it.nq == 2) scan_accumulate<ST, 2, U>(it, Q, d, c0, c1, lane, acc);
+    else scan_accumulate<ST, kQB, U>(it, Q, d, c0, c1, lane, acc);
+}
+
+template <int ST>
+__device__ __forceinline__ void finish_dispatch(const ScanItem& it, int d, const float (&acc)[kQB],
+                                                float* __restrict__ scores, float* __restrict__ bmax, int lane,
+                                                unsigned long long* __restrict__ qthr, int prune_blocks,
+                                                int prune_j) {
+    if (it.nq == 1) scan_finish<ST, 1>(it, d, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
+    else if (it.nq == 2) scan_finish<ST, 2>(it, d, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
+    else scan_finish<ST, kQB>(it, d, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
+}
+
+template <int ST, int U>
 __device__ __forceinline__ void scan_dispatch(const ScanItem& it, const float* __restrict__ Q,
                                               int d, float* __restrict__ scores,
                                               float* __restrict__ bmax, int lane,
                                               unsigned long long* __restrict__ qthr,
                                               int prune_blocks, int prune_j) {
-    if (it.nq == 1)
-        scan_item<ST, 1, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
-    else if (it.nq == 2)
-        scan_item<ST, 2, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
-    else
-        scan_item<ST, kQB, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
+    float acc[kQB];
+    accumulate_dispatch<ST, U>(it, Q, d, 0, d / Store<ST>::E, lane, acc);
+    finish_dispatch<ST>(it, d, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
+}
+
+// One item per group of SPLIT wavefronts of a 4-wavefront workgroup: wavefront p of the
+// group takes the chunks [nchunk*p/SPLIT, nchunk*(p+1)/SPLIT) of the block, the partial sums
+// meet in LDS and the first wavefront of the group adds them in ascending p and finishes the
+// item.  Items become SPLIT times shorter and SPLIT times as many, which shortens the last,
+// partly filled round of a plan with few items, and the wavefronts of a group read one
+// contiguous region side by side.  The order of the additions differs from the unsplit
+// kernel's, so an index uses one or the other throughout.
+template <int ST, int U, int SPLIT>
+__global__ __launch_bounds__(256) void k_scan_split(
+    const ScanItem* __restrict__ items, const unsigned long long* __restrict__ n_items_dev,
+    uint32_t n_items_host, const float* __restrict__ Q, int d, float* __restrict__ scores,
+    float* __restrict__ bmax, unsigned long long* __restrict__ qthr, int prune_blocks, int prune_j) {
+    static_assert(SPLIT == 2 || SPLIT == 4, "two or four wavefronts per item");
+    __shared__ float part[4][kQB][kLanes];
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t T = n_items_dev ? (uint32_t)*n_items_dev : n_items_host;
+    const uint32_t t = blockIdx.x * (4 / SPLIT) + wave / SPLIT;
+    const uint32_t p = wave % SPLIT;
+    const bool active = t < T;
+    ScanItem it = items[active ? t : 0];
+    float acc[kQB] = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+        const int nchunk = d / Store<ST>::E;
+        accumulate_dispatch<ST, U>(it, Q, d, (int)(nchunk * p / SPLIT), (int)(nchunk * (p + 1) / SPLIT), lane, acc);
+        if (p > 0) {
+#pragma unroll
+            for (int g = 0; g < kQB; ++g) part[wave][g][lane] = acc[g];
+        }
+    }
+    __syncthreads();
+    if (active && p == 0) {
+#pragma unroll
+        for (int o = 1; o < SPLIT; ++o)
+#pragma unroll
+            for (int g = 0; g < kQB; ++g) acc[g] += part[wave + o][g][lane];
+        finish_dispatch<ST>(it, d, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
+    }
 }
 
 constexpr int kScanWaves = 4;   // default wavefronts per workgroup of the scan
 
-// mode 0: one wavefront per item, grid sized by the host's upper bound on the items;
-// mode 1: persistent wavefronts pulling items from an atomic queue (*queue must be 0).
-// The item count comes from device memory (n_items_dev) when the plan was made on the
-// device, else from the host (n_items_host).
+// One wavefront per item; the grid is sized by the host's upper bound on the items and the
+// wavefronts beyond the real count leave at once.  The item count comes from device memory
+// (n_items_dev) when the plan was made on the device, else from the host (n_items_host).
 template <int ST, int U, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_scan(
     const ScanItem* __restrict__ items, const unsigned long long* __restrict__ n_items_dev,
     uint32_t n_items_host, const float* __restrict__ Q, int d, float* __restrict__ scores,
-    float* __restrict__ bmax, int mode, unsigned int* __restrict__ queue,
-    unsigned long long* __restrict__ qthr, int prune_blocks, int prune_j) {
+    float* __restrict__ bmax, unsigned long long* __restrict__ qthr, int prune_blocks, int prune_j) {
     const int lane = threadIdx.x & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t T = n_items_dev ? (uint32_t)*n_items_dev : n_items_host;
-    if (mode == 0) {
-        uint32_t t = blockIdx.x * WAVES + wave;
-        if (t >= T) return;
-        ScanItem it = items[t];
-        scan_dispatch<ST, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
-    } else {
-        for (;;) {
-            // All 64 lanes take part in the atomic (lane 0 adds 1, the others 0) so that
-            // no divergent branch surrounds the wave-uniform read below: with the ticket
-            // taken under `if (lane == 0)` the compiler split the loop per lane and the
-            // other 63 lanes kept re-running item 0.
-            uint32_t t = atomicAdd(queue, lane == 0 ? 1u : 0u);
-            t = __builtin_amdgcn_readfirstlane(t);
-            if (t >= T) break;           // every wavefront reaches this: the queue only grows
-            ScanItem it = items[t];
-            scan_dispatch<ST, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
-        }
-    }
+    const uint32_t t = blockIdx.x * WAVES + wave;
+    if (t >= T) return;
+    ScanItem it = items[t];
+    scan_dispatch<ST, U>(it, Q, d, scores, bmax, lane, qthr, prune_blocks, prune_j);
 }
 
 // Upload-time re-layout: row-major rows of a piece of the index -> blocked storage.

@@ -1,8 +1,10 @@
 // Retrieval worker: the retrieval half of a decoupled retrieve-then-generate pipeline
 // (paper Section 4.1: requests wait in a retrieval queue, a retrieval worker forms
 // batches on its own and puts the retrieved contexts into the queue of the generation
-// worker).  One host thread drains a request queue into ivf_search batches on its own
-// stream; finished results wait in a context queue until the consumer takes them.  The
+// worker).  One host thread drains a request queue into batches, keeps up to two of them
+// on the GPU at once (ivf_search_queued: the front stages of a batch run under the scan
+// of the batch before it); finished results wait in a context queue until the consumer
+// takes them.  The
 // batch size for the current backlog comes from the backlog-aware rule (Section 4.4),
 // fed by the worker's own timings.  Exports the ivf_worker_* part of include/ivf.h.
 #include <hip/hip_runtime.h>
@@ -54,37 +56,89 @@ struct ivf_worker {
 
 namespace {
 
-void worker_loop(ivf_worker* w) {
-    if (hipSetDevice(w->device) != hipSuccess) { std::lock_guard<std::mutex> g(w->mu); w->failed = true; w->fail_code = IVF_ERR_HIP; w->cv_res.notify_all(); return; }
+// One batch on its way through the GPU: its own stream, staging buffers and events, so
+// that the next batch can be issued while this one is still being searched.
+struct Slot {
     hipStream_t st = nullptr;
+    hipEvent_t ready = nullptr, done = nullptr;   // queries have landed; results have landed
     float *hq = nullptr, *dq = nullptr, *hs = nullptr, *ds = nullptr;
     int64_t *hi = nullptr, *di = nullptr;
-    const size_t B = (size_t)w->max_batch;
-    bool ok = hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&hq), B * w->d * sizeof(float)) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&hs), B * w->k * sizeof(float)) == hipSuccess &&
-              hipHostMalloc(reinterpret_cast<void**>(&hi), B * w->k * sizeof(int64_t)) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void**>(&dq), B * w->d * sizeof(float)) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void**>(&ds), B * w->k * sizeof(float)) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void**>(&di), B * w->k * sizeof(int64_t)) == hipSuccess;
+    std::vector<Request> batch;
+    bool busy = false;
+    std::chrono::steady_clock::time_point issued;
+};
+
+bool slot_init(Slot& s, size_t B, int d, int k) {
+    return hipStreamCreateWithFlags(&s.st, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&s.ready, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess &&
+           hipHostMalloc(reinterpret_cast<void**>(&s.hq), B * d * sizeof(float)) == hipSuccess &&
+           hipHostMalloc(reinterpret_cast<void**>(&s.hs), B * k * sizeof(float)) == hipSuccess &&
+           hipHostMalloc(reinterpret_cast<void**>(&s.hi), B * k * sizeof(int64_t)) == hipSuccess &&
+           hipMalloc(reinterpret_cast<void**>(&s.dq), B * d * sizeof(float)) == hipSuccess &&
+           hipMalloc(reinterpret_cast<void**>(&s.ds), B * k * sizeof(float)) == hipSuccess &&
+           hipMalloc(reinterpret_cast<void**>(&s.di), B * k * sizeof(int64_t)) == hipSuccess;
+}
+
+void slot_free(Slot& s) {
+    if (s.st) { (void)hipStreamSynchronize(s.st); (void)hipStreamDestroy(s.st); }
+    if (s.ready) (void)hipEventDestroy(s.ready);
+    if (s.done) (void)hipEventDestroy(s.done);
+    if (s.hq) (void)hipHostFree(s.hq);
+    if (s.hs) (void)hipHostFree(s.hs);
+    if (s.hi) (void)hipHostFree(s.hi);
+    if (s.dq) (void)hipFree(s.dq);
+    if (s.ds) (void)hipFree(s.ds);
+    if (s.di) (void)hipFree(s.di);
+}
+
+// Copies the batch's queries to the device and queues the search and the copies back.
+int slot_issue(ivf_worker* w, Slot& s) {
+    const size_t nb = s.batch.size();
+    for (size_t i = 0; i < nb; ++i) std::memcpy(s.hq + i * w->d, s.batch[i].q.data(), sizeof(float) * w->d);
+    s.issued = std::chrono::steady_clock::now();
+    if (hipMemcpyAsync(s.dq, s.hq, nb * w->d * sizeof(float), hipMemcpyHostToDevice, s.st) != hipSuccess ||
+        hipEventRecord(s.ready, s.st) != hipSuccess)
+        return IVF_ERR_HIP;
+    // the search reads the queries behind `ready`, not behind the stream: its front stages
+    // run under the scan of the batch issued before it
+    int rc = ivf_search_queued(w->idx, s.dq, (int64_t)nb, w->nprobe, w->k, s.di, s.ds, s.st, s.ready);
+    if (rc) return rc;
+    if (hipMemcpyAsync(s.hi, s.di, nb * w->k * sizeof(int64_t), hipMemcpyDeviceToHost, s.st) != hipSuccess ||
+        hipMemcpyAsync(s.hs, s.ds, nb * w->k * sizeof(float), hipMemcpyDeviceToHost, s.st) != hipSuccess ||
+        hipEventRecord(s.done, s.st) != hipSuccess)
+        return IVF_ERR_HIP;
+    s.busy = true;
+    return 0;
+}
+
+void worker_loop(ivf_worker* w) {
+    if (hipSetDevice(w->device) != hipSuccess) { std::lock_guard<std::mutex> g(w->mu); w->failed = true; w->fail_code = IVF_ERR_HIP; w->cv_res.notify_all(); return; }
+    constexpr int kSlots = 2;                      // batches in flight
+    Slot slots[kSlots];
+    bool ok = true;
+    for (int i = 0; ok && i < kSlots; ++i) ok = slot_init(slots[i], (size_t)w->max_batch, w->d, w->k);
     std::vector<int64_t> cands;
     for (int b = 1; b <= w->max_batch; b <<= 1) cands.push_back(b);
     if (cands.back() != w->max_batch) cands.push_back(w->max_batch);
-    std::vector<Request> batch;
     bool moving = false, started = false, finish = false;
     int64_t budget = -1;
+    int head = 0, inflight = 0;                    // slots[head] is the oldest batch in flight
+    auto last_done = std::chrono::steady_clock::now();
+    int fail_rc = 0;
     while (ok) {
-        batch.clear();
         {
             std::unique_lock<std::mutex> lk(w->mu);
             auto wake = [&] { return w->stopping || !w->requests.empty() || w->wanted_budget >= 0; };
-            if (moving) w->cv_req.wait_for(lk, std::chrono::milliseconds(1), wake);   // an idle worker keeps the change going
-            else w->cv_req.wait(lk, wake);
+            if (inflight == 0) {                   // nothing to collect: sleep until there is something to do
+                if (moving) w->cv_req.wait_for(lk, std::chrono::milliseconds(1), wake);   // an idle worker keeps the change going
+                else w->cv_req.wait(lk, wake);
+            }
             if (w->wanted_budget >= 0) {
                 budget = w->wanted_budget;
                 w->wanted_budget = -1;
             }
-            finish = w->stopping && w->requests.empty();
+            finish = w->stopping && w->requests.empty() && inflight == 0;
         }
         if (budget >= 0 || moving) {
             // budget changes run beside the searches: start one between two batches, then
@@ -109,82 +163,84 @@ void worker_loop(ivf_worker* w) {
             w->st.budget_error = brc;
             if (have_info) w->st.resident_lists = info.resident_lists;
         }
-        {
-            std::unique_lock<std::mutex> lk(w->mu);
-            if (w->requests.empty()) {
-                if (w->stopping && !moving && w->wanted_budget < 0) break;   // stopping and drained
-                continue;
-            }
-            const int64_t n = (int64_t)w->requests.size();
-            // batch size for this backlog: the backlog-aware rule once two batch sizes have
-            // been timed, the whole backlog (up to max_batch) before that
-            int64_t take = std::min<int64_t>(n, w->max_batch);
-            std::vector<double> bs, ts;
-            for (size_t i = 0; i < cands.size(); ++i)
-                if (w->t_n[i] > 0) { bs.push_back((double)cands[i]); ts.push_back(w->t_ms[i]); }
-            if (bs.size() >= 2) {
-                double a = 0, c = 0;
-                if (ivf_sched_fit(bs.data(), ts.data(), (int)bs.size(), &a, &c) == 0 && a > 0 && c >= 0) {
-                    int64_t best = take;
-                    if (ivf_sched_choose(a, c, n, cands.data(), (int)cands.size(), 0.0, &best, nullptr) == 0)
-                        take = std::min<int64_t>(std::min<int64_t>(best, n), w->max_batch);
-                    w->st.fit_a_ms = a;
-                    w->st.fit_c = c;
+        // issue a batch if there are requests and a free slot
+        bool issued = false;
+        if (inflight < kSlots) {
+            Slot& s = slots[(head + inflight) % kSlots];
+            s.batch.clear();
+            {
+                std::unique_lock<std::mutex> lk(w->mu);
+                if (!w->requests.empty()) {
+                    const int64_t n = (int64_t)w->requests.size();
+                    // batch size for this backlog: the backlog-aware rule once two batch sizes have
+                    // been timed, the whole backlog (up to max_batch) before that
+                    int64_t take = std::min<int64_t>(n, w->max_batch);
+                    std::vector<double> bs, ts;
+                    for (size_t i = 0; i < cands.size(); ++i)
+                        if (w->t_n[i] > 0) { bs.push_back((double)cands[i]); ts.push_back(w->t_ms[i]); }
+                    if (bs.size() >= 2) {
+                        double a = 0, c = 0;
+                        if (ivf_sched_fit(bs.data(), ts.data(), (int)bs.size(), &a, &c) == 0 && a > 0 && c >= 0) {
+                            int64_t best = take;
+                            if (ivf_sched_choose(a, c, n, cands.data(), (int)cands.size(), 0.0, &best, nullptr) == 0)
+                                take = std::min<int64_t>(std::min<int64_t>(best, n), w->max_batch);
+                            w->st.fit_a_ms = a;
+                            w->st.fit_c = c;
+                        }
+                    }
+                    for (int64_t i = 0; i < take; ++i) {
+                        s.batch.push_back(std::move(w->requests.front()));
+                        w->requests.pop_front();
+                    }
+                } else if (inflight == 0 && w->stopping && !moving && w->wanted_budget < 0) {
+                    break;                                          // stopping and drained
                 }
             }
-            for (int64_t i = 0; i < take; ++i) {
-                batch.push_back(std::move(w->requests.front()));
-                w->requests.pop_front();
+            if (!s.batch.empty()) {
+                if ((fail_rc = slot_issue(w, s))) break;
+                inflight += 1;
+                issued = true;
             }
         }
-        const size_t nb = batch.size();
-        for (size_t i = 0; i < nb; ++i) std::memcpy(hq + i * w->d, batch[i].q.data(), sizeof(float) * w->d);
-        const auto t0 = std::chrono::steady_clock::now();
-        int rc = 0;
-        if (hipMemcpyAsync(dq, hq, nb * w->d * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess) rc = IVF_ERR_HIP;
-        if (!rc) rc = ivf_search(w->idx, dq, (int64_t)nb, w->nprobe, w->k, di, ds, st);
-        if (!rc && (hipMemcpyAsync(hi, di, nb * w->k * sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
-                    hipMemcpyAsync(hs, ds, nb * w->k * sizeof(float), hipMemcpyDeviceToHost, st) != hipSuccess ||
-                    hipStreamSynchronize(st) != hipSuccess))
-            rc = IVF_ERR_HIP;
-        const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
-        std::lock_guard<std::mutex> g(w->mu);
-        if (rc) {
-            w->failed = true;
-            w->fail_code = rc;
+        // collect the oldest batch when nothing new could be issued (both slots taken, or no
+        // request waiting): its service time runs from the later of its issue and the
+        // completion of the batch before it
+        if (inflight > 0 && !issued) {
+            Slot& s = slots[head];
+            if (hipEventSynchronize(s.done) != hipSuccess) { fail_rc = IVF_ERR_HIP; break; }
+            const auto now = std::chrono::steady_clock::now();
+            const double ms = std::chrono::duration<double, std::milli>(now - std::max(s.issued, last_done)).count();
+            last_done = now;
+            const size_t nb = s.batch.size();
+            std::lock_guard<std::mutex> g(w->mu);
+            for (size_t i = 0; i < nb; ++i) {
+                Result r;
+                r.ids.assign(s.hi + i * w->k, s.hi + (i + 1) * w->k);
+                r.scores.assign(s.hs + i * w->k, s.hs + (i + 1) * w->k);
+                w->done.emplace(s.batch[i].ticket, std::move(r));
+            }
+            // time of a batch of this size, filed under the smallest candidate that holds it
+            size_t slot = 0;
+            while (slot + 1 < cands.size() && (int64_t)nb > cands[slot]) ++slot;
+            w->t_ms[slot] = w->t_n[slot] ? 0.75 * w->t_ms[slot] + 0.25 * ms : ms;
+            w->t_n[slot] += 1;
+            w->st.batches += 1;
+            w->st.requests_done += (int64_t)nb;
+            w->st.largest_batch = std::max<int64_t>(w->st.largest_batch, (int64_t)nb);
             w->cv_res.notify_all();
-            break;
+            s.busy = false;
+            head = (head + 1) % kSlots;
+            inflight -= 1;
         }
-        for (size_t i = 0; i < nb; ++i) {
-            Result r;
-            r.ids.assign(hi + i * w->k, hi + (i + 1) * w->k);
-            r.scores.assign(hs + i * w->k, hs + (i + 1) * w->k);
-            w->done.emplace(batch[i].ticket, std::move(r));
-        }
-        // time of a batch of this size, filed under the smallest candidate that holds it
-        size_t slot = 0;
-        while (slot + 1 < cands.size() && (int64_t)nb > cands[slot]) ++slot;
-        w->t_ms[slot] = w->t_n[slot] ? 0.75 * w->t_ms[slot] + 0.25 * ms : ms;
-        w->t_n[slot] += 1;
-        w->st.batches += 1;
-        w->st.requests_done += (int64_t)nb;
-        w->st.largest_batch = std::max<int64_t>(w->st.largest_batch, (int64_t)nb);
-        w->cv_res.notify_all();
     }
-    if (!ok) {
+    if (!ok || fail_rc) {
         std::lock_guard<std::mutex> g(w->mu);
         w->failed = true;
-        w->fail_code = IVF_ERR_OOM_DEVICE;
+        w->fail_code = fail_rc ? fail_rc : IVF_ERR_OOM_DEVICE;
         w->cv_res.notify_all();
     }
     (void)hipGetLastError();
-    if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
-    if (hq) (void)hipHostFree(hq);
-    if (hs) (void)hipHostFree(hs);
-    if (hi) (void)hipHostFree(hi);
-    if (dq) (void)hipFree(dq);
-    if (ds) (void)hipFree(ds);
-    if (di) (void)hipFree(di);
+    for (int i = 0; i < kSlots; ++i) slot_free(slots[i]);
 }
 
 }  // namespace

@@ -17,12 +17,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libivf_mi355x.so")
 
-IVF_FP32, IVF_FP16, IVF_INT8 = 0, 1, 2
+IVF_FP32, IVF_FP16, IVF_INT8, IVF_PQ8 = 0, 1, 2, 3
 STAGES = ("coarse", "probe", "regroup", "scan", "stream", "select", "total")
 
 EXPORTS = (
     "ivf_index_create", "ivf_index_destroy", "ivf_index_upload", "ivf_index_upload_begin",
     "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
+    "ivf_search_queued", "ivf_index_set_pq_codebooks",
     "ivf_set_device_budget_async", "ivf_budget_progress", "ivf_budget_wait", "ivf_worker_set_device_budget",
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
@@ -89,12 +90,14 @@ def load_library() -> C.CDLL:
     lib.ivf_index_upload_begin.argtypes = [vp, i32, i64, i64, vp, i32, vp]
     lib.ivf_index_upload_lists.argtypes = [vp, i64, i64, vp, vp]
     lib.ivf_index_upload_end.argtypes = [vp]
+    lib.ivf_index_set_pq_codebooks.argtypes = [vp, i32, i32, vp]
     lib.ivf_set_device_budget.argtypes = [vp, i64]
     lib.ivf_set_device_budget_async.argtypes = [vp, i64]
     lib.ivf_budget_progress.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i32)]
     lib.ivf_budget_wait.argtypes = [vp]
     lib.ivf_worker_set_device_budget.argtypes = [vp, i64]
     lib.ivf_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    lib.ivf_search_queued.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
     lib.ivf_last_error.restype = C.c_char_p
     lib.ivf_get_info.argtypes = [vp, C.POINTER(Info)]
     lib.ivf_debug_last_probes.argtypes = [vp, vp, vp]
@@ -180,11 +183,18 @@ class Index:
             pass
 
     # ---- upload
-    def upload(self, centroids, vectors, ids, list_offsets):
+    def set_pq_codebooks(self, codebooks):
+        """codebooks: float32 [m, 256, d/m] (NumPy or torch); uploads with dtype IVF_PQ8 follow."""
+        m, ncode, dsub = codebooks.shape
+        assert ncode == 256 and str(codebooks.dtype).endswith("float32")
+        _check(self._lib.ivf_index_set_pq_codebooks(self._h, m * dsub, m, _ptr(codebooks)))
+
+    def upload(self, centroids, vectors, ids, list_offsets, dtype: Optional[int] = None):
+        """dtype: by the array type if None (uint8 = int8 records; pass IVF_PQ8 for code bytes)."""
         nlist, d = centroids.shape
         n = vectors.shape[0]
-        dt = _dtype_code(vectors)
-        assert vectors.shape[1] == (d + 4 if dt == IVF_INT8 else d)
+        dt = _dtype_code(vectors) if dtype is None else dtype
+        assert dt == IVF_PQ8 or vectors.shape[1] == (d + 4 if dt == IVF_INT8 else d)
         assert ids.shape[0] == n and list_offsets.shape[0] == nlist + 1
         _check(self._lib.ivf_index_upload(self._h, d, nlist, n, _ptr(centroids), _ptr(vectors),
                                           dt, _ptr(ids), _ptr(list_offsets)))
@@ -232,6 +242,22 @@ class Index:
                                     _ptr(out_scores), _stream_handle(stream)))
         return out_ids, out_scores
 
+    def search_queued(self, queries, nprobe: int, k: int, out_ids=None, out_scores=None, stream=None,
+                      queries_ready=None):
+        """ivf_search_queued: as `search`, but `queries` is read as soon as `queries_ready`
+        (a torch.cuda.Event, or None = now) allows, not behind earlier work on `stream`."""
+        import torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        nq = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        if out_scores is None:
+            out_scores = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        ev = None if queries_ready is None else queries_ready.cuda_event
+        _check(self._lib.ivf_search_queued(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
+                                           _ptr(out_scores), _stream_handle(stream), ev))
+        return out_ids, out_scores
+
     def search_raw(self, queries_ptr, nq, nprobe, k, out_ids_ptr, out_scores_ptr, stream_ptr=None) -> int:
         """The C call with raw addresses, returning the status code (for error-path tests)."""
         return self._lib.ivf_search(self._h, queries_ptr, nq, nprobe, k, out_ids_ptr, out_scores_ptr, stream_ptr)
@@ -257,7 +283,9 @@ class Index:
     def read_list(self, list_no: int, d: int, dtype: int):
         ln = C.c_int64()
         _check(self._lib.ivf_debug_read_list(self._h, list_no, None, None, C.byref(ln)))
-        if dtype == IVF_INT8:
+        if dtype == IVF_PQ8:
+            vec = np.empty((ln.value, d), dtype=np.uint8)            # d = code bytes per vector here
+        elif dtype == IVF_INT8:
             vec = np.empty((ln.value, d + 4), dtype=np.uint8)
         else:
             vec = np.empty((ln.value, d), dtype=np.float16 if dtype == IVF_FP16 else np.float32)

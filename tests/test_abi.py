@@ -44,7 +44,7 @@ def test_null_arguments_return_error_codes_without_a_gpu():
     assert lib.ivf_budget_wait(None) == -1
     assert lib.ivf_worker_set_device_budget(None, 0) == -1
     assert lib.ivf_index_upload_end(None) == -1
-    assert lib.ivf_set_option(None, b"scan_mode", 0) == -1
+    assert lib.ivf_set_option(None, b"scan_unroll", 8) == -1
     assert lib.ivf_worker_start(None, 1, 1, 1, None) == -1
     assert lib.ivf_worker_submit(None, None, None) == -1
     assert lib.ivf_worker_wait(None, 1, None, None, 0) == -1

@@ -118,7 +118,7 @@ def test_int8_edge_cases_match_oracle(case):
     say(f"int8 {name}: n={n} d={d} nlist={nlist} nq={nq} nprobe={nprobe} k={k}")
     got = gpu_search(idx, q, nprobe, k)
     check_against_oracle(cen, rec, ids, off, q, nprobe, k, got, "int8", abs_floor=_floor(q, rec))
-    for option, value in (("scan_unroll", 8), ("scan_mode", 1), ("scan_waves", 1)):
+    for option, value in (("scan_unroll", 8), ("scan_waves", 8), ("scan_waves", 1)):
         idx.set_option(option, value)
         again = gpu_search(idx, q, nprobe, k)
         assert np.array_equal(again[0], got[0]) and np.array_equal(again[1], got[1]), option

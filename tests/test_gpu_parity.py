@@ -165,6 +165,28 @@ def test_many_queries_share_one_list():
     idx.close()
 
 
+def test_skewed_batch_sixteen_queries_per_list(c1):
+    """A batch whose 128 queries come from 8 mixture components: every home list is probed
+    by about 16 queries (the other probes of a query depend on its noise and are shared
+    less), so its blocks are shared by several groups of four queries."""
+    w, h, idx = c1
+    q = W.queries(w, batch=9, nq=128, components=8)
+    say("C1 skewed: nq=128 from 8 components, nprobe=8 k=10")
+    got = gpu_search(idx, q, w.nprobe, w.k)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, w.k, got, w.storage)
+    st = idx.last_search_stats()
+    probes = got[2]
+    cnt = np.bincount(probes.ravel(), minlength=w.nlist)
+    nblk = (np.diff(h.offsets) + 63) // 64
+    assert st.pairs == 128 * w.nprobe and st.unique_lists == int((cnt > 0).sum())
+    assert (cnt >= 12).sum() >= 8 and st.pairs / st.unique_lists >= 3      # really skewed
+    assert st.scan_items == int((nblk * ((cnt + 3) // 4)).sum())   # one item per block and group of 4 queries
+    # the same rows when each query is searched in a batch of its own component only
+    sub = q[::16]
+    one = gpu_search(idx, sub, w.nprobe, w.k)
+    assert np.array_equal(one[0], got[0][::16]) and np.array_equal(one[1], got[1][::16])
+
+
 @pytest.mark.parametrize("nq", [33, 64, 65, 129, 300])
 def test_batch_sizes_across_the_coarse_kernel_tilings(c1, nq):
     """nq <= 32, <= 64 and above take different query-tile shapes in the coarse kernel;
@@ -405,19 +427,65 @@ def test_scan_launch_options_agree(c1):
     q = W.queries(w, batch=5)
     ref = gpu_search(idx, q, w.nprobe, w.k)
     try:
-        for mode, unroll, waves in [(0, 8, 4), (0, 16, 4), (1, 8, 4), (1, 16, 4), (0, 16, 1), (0, 16, 2),
-                                    (0, 8, 8), (1, 16, 2)]:
-            say(f"C1 scan_mode={mode} scan_unroll={unroll} scan_waves={waves}")
-            idx.set_option("scan_mode", mode)
+        # register-buffer width and workgroup size never change the order of the additions;
+        # the number of wavefronts per block does (last bits of the scores only)
+        for split, unroll, waves in [(0, 8, 4), (0, 16, 4), (1, 8, 4), (1, 16, 4), (1, 16, 1), (1, 16, 2),
+                                     (1, 8, 8), (2, 16, 4), (2, 8, 4), (4, 8, 4)]:
+            say(f"C1 scan_split={split} scan_unroll={unroll} scan_waves={waves}")
+            idx.set_option("scan_split", split)
             idx.set_option("scan_unroll", unroll)
             idx.set_option("scan_waves", waves)
             got = gpu_search(idx, q, w.nprobe, w.k)
             assert np.array_equal(got[0], ref[0])
-            assert np.allclose(got[1], ref[1], rtol=1e-6)
+            if split in (0, 2):                      # C1's blocks (96 KiB) take two wavefronts by default
+                assert np.array_equal(got[1], ref[1])
+            else:
+                assert np.allclose(got[1], ref[1], rtol=1e-6)
     finally:
-        idx.set_option("scan_mode", 0)
+        idx.set_option("scan_split", 0)
         idx.set_option("scan_unroll", 16)
         idx.set_option("scan_waves", 4)
+
+
+SPLIT_CASES = [
+    # name, n, d, nlist, storage, nq, nprobe, k: dimensions whose chunks split evenly, unevenly and not at all
+    ("split_d768_fp16", 6000, 768, 9, "fp16", 11, 3, 20),
+    ("split_d768_fp32", 4000, 768, 7, "fp32", 6, 3, 100),
+    ("split_d8", 900, 8, 5, "fp16", 7, 2, 10),
+    ("split_d40_fp32", 3000, 40, 7, "fp32", 9, 3, 10),
+    ("split_d200_fp16", 3000, 200, 6, "fp16", 23, 6, 64),
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=[c[0] for c in SPLIT_CASES])
+def test_scan_with_several_wavefronts_per_block_matches_oracle(case):
+    """scan_split = 2 | 4: the dimensions of a block are shared out over wavefronts and the
+    partial sums added in LDS (another order of additions than one wavefront per block:
+    compared with the oracle, not bit for bit with the unsplit scan), with and without
+    store pruning, in both host-list modes."""
+    name, n, d, nlist, storage, nq, nprobe, k = case
+    cen, vec, ids, off = _random_index(zlib.crc32(name.encode()) % 1000, n, d, nlist, storage, normalise=True)
+    rng = np.random.default_rng(17)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    q[:nq // 2] = cen[rng.integers(0, nlist, nq // 2)] + 0.1 * q[:nq // 2]      # several queries per list
+    idx = ivf.Index()
+    idx.upload(cen, vec, ids, off)
+    for split in (2, 4):
+        idx.set_option("scan_split", split)
+        for prune in (1, 2):
+            idx.set_option("scan_prune", prune)
+            say(f"{name}: scan_split={split} scan_prune={prune}")
+            got = gpu_search(idx, q, nprobe, k)
+            check_against_oracle(cen, vec, ids, off, q, nprobe, k, got, storage, abs_floor=_floor(q, vec))
+        idx.set_device_budget(idx.info().index_bytes // 2)
+        part = gpu_search(idx, q, nprobe, k)
+        assert np.array_equal(part[0], got[0]) and np.array_equal(part[1], got[1])
+        idx.set_option("host_direct", 0)
+        staged = gpu_search(idx, q, nprobe, k)
+        assert np.array_equal(staged[0], got[0]) and np.array_equal(staged[1], got[1])
+        idx.set_option("host_direct", 1)
+        idx.set_device_budget(2**62)
+    idx.close()
 
 
 @pytest.mark.parametrize("k", [1, 10, 64, 65, 100, 128, 129])

@@ -95,7 +95,7 @@ def test_random_walk_over_the_library_state(seed, storage):
                 idx.set_option("host_direct", direct)
                 idx.set_option("stage_mb", int(rng.choice([1, 4, 64])))
         elif op < 95:
-            name, values = [("scan_unroll", (8, 16)), ("scan_waves", (1, 2, 4, 8)), ("scan_mode", (0, 1)),
+            name, values = [("scan_unroll", (8, 16)), ("scan_waves", (1, 2, 4, 8)), ("nside", (1, 2, 3)),
                             ("scan_prune", (0, 1, 2)), ("sel_threads", (0, 256, 1024)),
                             ("regroup_fused", (0, 1))][int(rng.integers(0, 6))]
             v = int(rng.choice(values))
