@@ -233,6 +233,31 @@ int ivf_search(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int
 int ivf_search_queued(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int k,
                       int64_t *out_ids, float *out_scores, void *stream, void *queries_ready);
 
+/*
+ * ivf_search_noalloc — ivf_search for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results, but the search scratch (coarse
+ * scores, probe tables, scan items, score blocks) is carved from a static device array
+ * of 64 MiB inside the library instead of being allocated on first use; the call never
+ * allocates or frees memory.  Each GPU on which the library creates an index holds its
+ * own copy of that array until the process ends.
+ *   - A search that needs more returns IVF_ERR_LIMIT with the size in the message; the
+ *     need is about 4*nq*nlist bytes plus 292 bytes per 64-vector block of nq times the
+ *     nprobe longest lists (the benchmark's 100k, 2M and 20M-vector configurations fit,
+ *     the 100M one with 128 queries does not).
+ *   - IVF_ERR_INVALID while a budget change is under way (it allocates and frees pool
+ *     segments) and in the staged host-list mode ("host_direct" = 0: staging buffers);
+ *     host-resident lists read in place are fine.
+ *   - The array is shared by every index on the GPU and keeps the last call's contents
+ *     (what must start at zero is cleared by the search itself).  Calls issued one after
+ *     the other are ordered on the device by the library, whatever their streams and
+ *     indexes; calls that overlap on one GPU from several host threads are serialised by
+ *     a lock while they are issued, but the introspection calls (ivf_debug_last_*,
+ *     ivf_last_search_stats) then read whatever search used the array last.
+ */
+int ivf_search_noalloc(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int k,
+                       int64_t *out_ids, float *out_scores, void *stream);
+
 /* Thread-local message of the last error on this thread ("" if none). */
 const char *ivf_last_error(void);
 

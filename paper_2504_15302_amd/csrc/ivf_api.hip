@@ -4,10 +4,46 @@
 #include "ivf_host.h"
 #include "ivf_moves.h"
 
+#include <mutex>
+
+// Scratch memory of ivf_search_noalloc: one array per GPU that loads the library, held
+// until the process ends and shared by every index on that GPU.  In host code the name
+// is only a handle for hipGetSymbolAddress; kernels get the address looked up there.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+struct StaticScratchDevice {
+    char* base = nullptr;            // device address of `scratch` on this GPU
+    hipEvent_t last_use = nullptr;   // behind the last search that used the array
+    bool used = false;
+};
+StaticScratchDevice g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+// Looks the array's address up once per device (the device must be current).
+int static_scratch_init(int device) {
+    if (device < 0 || device >= kMaxDevices) return fail(IVF_ERR_LIMIT, "HIP device %d: at most %d devices", device, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticScratchDevice& dv = g_static[device];
+    if (dv.base) return 0;
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(IVF_ERR_HIP, "hipGetSymbolAddress gave no address for the static scratch array");
+    HIP_TRY(hipEventCreateWithFlags(&dv.last_use, hipEventDisableTiming));
+    dv.base = static_cast<char*>(ptr);
+    return 0;
+}
 
 void free_scratch(Scratch& s) {
     const hipEvent_t end = s.end;                // the index's, not the buffers'
+    if (s.carved) {                              // slices of a region that is not ours to free
+        s = Scratch();
+        s.end = end;
+        return;
+    }
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
     dfree(s.sblk_start); dfree(s.item_start); dfree(s.wg_totals); dfree(s.pair_flat);
     dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
@@ -38,6 +74,7 @@ void free_index_data(ivf_index* x) {
     pool_free_all(x->hpool);
     free_staging(x);
     for (int p = 0; p < kSets; ++p) free_scratch(x->sc[p]);
+    free_scratch(x->sc_static);
     x->last_sc = nullptr;
     x->last_nq = 0;
     x->ready = x->uploading = false;
@@ -131,6 +168,53 @@ int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offloa
         }
     }
     return 0;
+}
+
+// The same buffers as slices of one region that the caller owns (256-byte aligned, in a
+// fixed order).  Returns the bytes the search needs; `s` is filled only if they fit in `cap`.
+size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, size_t cap, Scratch& s) {
+    const size_t nlist = (size_t)x->nlist;
+    const size_t ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
+    const size_t npairs = (size_t)nq * nprobe;
+    const size_t nblocks = (size_t)std::max<int64_t>(1, block_bound(x, nq, nprobe));
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += (std::max<size_t>(bytes, 256) + 255) & ~(size_t)255;
+        return o;
+    };
+    const size_t o_S = take(4 * (size_t)nq * nlist), o_tmax = take(4 * (size_t)nq * ntile);
+    const size_t o_zero = take(4 * (2 * nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq));
+    const size_t o_wg = take(4 * kScanVals * ((nlist + kScanThreads - 1) / kScanThreads));
+    const size_t o_ps = take(4 * nlist), o_sb = take(4 * nlist), o_is = take(4 * nlist);
+    const size_t o_pr = take(4 * npairs), o_pf = take(4 * npairs), o_pp = take(4 * npairs);
+    const size_t o_it = take(sizeof(ScanItem) * nblocks), o_sc = take(4 * nblocks * kLanes), o_bm = take(4 * nblocks);
+    const size_t o_pq = x->dtype == IVF_PQ8 ? take(4 * (size_t)nq * x->pq_m * 256) : 0;
+    if (off > cap) return off;
+    const hipEvent_t end = s.end;
+    const bool end_recorded = s.end_recorded;
+    s = Scratch();
+    s.end = end;
+    s.end_recorded = end_recorded;
+    s.carved = true;
+    s.S = reinterpret_cast<float*>(base + o_S);
+    s.tmax = reinterpret_cast<float*>(base + o_tmax);
+    s.zeroed = reinterpret_cast<int*>(base + o_zero);
+    s.counters = reinterpret_cast<unsigned long long*>(s.zeroed + 2 * nlist + 16);
+    s.qthr = s.counters + kNumCounters;
+    s.wg_totals = reinterpret_cast<uint32_t*>(base + o_wg);
+    s.pair_start = reinterpret_cast<uint32_t*>(base + o_ps);
+    s.sblk_start = reinterpret_cast<uint32_t*>(base + o_sb);
+    s.item_start = reinterpret_cast<uint32_t*>(base + o_is);
+    s.probes = reinterpret_cast<int32_t*>(base + o_pr);
+    s.pair_flat = reinterpret_cast<uint32_t*>(base + o_pf);
+    s.pair_of_probe = reinterpret_cast<uint32_t*>(base + o_pp);
+    s.items = reinterpret_cast<ScanItem*>(base + o_it);
+    s.scores = reinterpret_cast<float*>(base + o_sc);
+    s.bmax = reinterpret_cast<float*>(base + o_bm);
+    if (x->dtype == IVF_PQ8) s.pq_tables = reinterpret_cast<float*>(base + o_pq);
+    s.bytes = off;
+    return off;
 }
 
 // One search as the launch sequence sees it.
@@ -636,6 +720,7 @@ int ivf_index_create(ivf_index** out) {
         if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_scan[i], hipEventDisableTiming);
         if (e == hipSuccess && i > 0) e = hipEventCreateWithFlags(&x->sc[i].end, hipEventDisableTiming);
     }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&x->sc_static.end, hipEventDisableTiming);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&x->h_counters), sizeof(unsigned long long) * kNumCounters);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_search_end, hipEventDisableTiming);
     x->sc[0].end = x->ev_search_end;
@@ -653,6 +738,14 @@ int ivf_index_create(ivf_index** out) {
         return rc;
     }
     x->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // the static scratch array of ivf_search_noalloc: its address on this device, looked up once
+    if (int rc = static_scratch_init(x->device)) {
+        std::string msg = g_err;
+        ivf_index_destroy(x);
+        g_err = msg;
+        return rc;
+    }
+    x->static_base = g_static[x->device].base;
     *out = x;
     return 0;
 }
@@ -674,6 +767,7 @@ void ivf_index_destroy(ivf_index* x) {
         if (x->ev_scan[i]) (void)hipEventDestroy(x->ev_scan[i]);
         if (i > 0 && x->sc[i].end) (void)hipEventDestroy(x->sc[i].end);
     }
+    if (x->sc_static.end) (void)hipEventDestroy(x->sc_static.end);
     if (x->h_counters) (void)hipHostFree(x->h_counters);
     if (x->ev_search_end) (void)hipEventDestroy(x->ev_search_end);
     for (hipEvent_t e : x->spare_events) (void)hipEventDestroy(e);
@@ -1092,6 +1186,33 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
         x->timed_searches += 1;
     }
     return 0;
+}
+
+int ivf_search_noalloc(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
+                       float* out_scores, void* stream) {
+    SearchCtx c;
+    int rc = search_args(x, queries, nq, nprobe, k, out_ids, out_scores, c);
+    if (rc) return rc < 0 ? rc : 0;
+    if (moves_active(x))
+        return fail(IVF_ERR_INVALID, "ivf_search_noalloc: a budget change is under way (it allocates and frees pool segments)");
+    if (c.offload)
+        return fail(IVF_ERR_INVALID, "ivf_search_noalloc: the staged host-list mode needs staging buffers; use host_direct = 1");
+    if (!x->static_base) return fail(IVF_ERR_HIP, "ivf_search_noalloc: the static scratch array has no address on this device");
+    Scratch& s = x->sc_static;
+    const size_t need = carve_scratch(x, c.nq, c.nprobe, x->static_base, kStaticScratchBytes, s);
+    if (need > kStaticScratchBytes)
+        return fail(IVF_ERR_LIMIT, "ivf_search_noalloc: this search needs %zu bytes of scratch, the static array holds %zu "
+                    "(nq*nlist coarse scores plus 292 bytes per 64-vector block of nq times the nprobe longest lists)",
+                    need, (size_t)kStaticScratchBytes);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // every index on this GPU shares the array: this search starts behind the last one that used it
+    StaticScratchDevice& dv = g_static[x->device];
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (dv.used) HIP_TRY(hipStreamWaitEvent(st, dv.last_use, 0));
+    rc = search_serial(x, s, c, st);
+    if (hipEventRecord(dv.last_use, st) == hipSuccess) dv.used = true;
+    else { (void)hipGetLastError(); (void)hipStreamSynchronize(st); }
+    return rc;
 }
 
 int ivf_get_info(ivf_index* x, ivf_info* out) {

@@ -113,6 +113,7 @@ struct Scratch {
     ScanItem* h_items = nullptr;
     size_t h_items_cap = 0;
     size_t bytes = 0;
+    bool carved = false;            // buffers are slices of one caller-owned region: never freed one by one
     // Recorded behind the last kernel of the last search that used this set, on whatever
     // stream that was: the next search that uses the set starts behind it.  The handle
     // belongs to the index and outlives the buffers.
@@ -209,6 +210,8 @@ struct ivf_index {
     bool done_recorded = false;
     // search state
     Scratch sc[kSets];                 // queued searches go round the sets; searches on one stream use set 0
+    Scratch sc_static;                 // slices of the per-device static array (ivf_search_noalloc)
+    char* static_base = nullptr;       // device address of that array on this index's device
     Scratch* last_sc = nullptr;        // set of the last search (introspection calls read it)
     unsigned long long* h_counters = nullptr;   // pinned landing place of a set's counters
     int prune_blocks = 0, prune_j = 0;   // bound kept by the scan for the current search (see k_scan)

@@ -23,7 +23,7 @@ STAGES = ("coarse", "probe", "regroup", "scan", "stream", "select", "total")
 EXPORTS = (
     "ivf_index_create", "ivf_index_destroy", "ivf_index_upload", "ivf_index_upload_begin",
     "ivf_index_upload_lists", "ivf_index_upload_end", "ivf_set_device_budget", "ivf_search",
-    "ivf_search_queued", "ivf_index_set_pq_codebooks",
+    "ivf_search_queued", "ivf_search_noalloc", "ivf_index_set_pq_codebooks",
     "ivf_set_device_budget_async", "ivf_budget_progress", "ivf_budget_wait", "ivf_worker_set_device_budget",
     "ivf_last_error", "ivf_get_info", "ivf_debug_last_probes", "ivf_debug_last_coarse",
     "ivf_debug_read_list", "ivf_last_search_stats", "ivf_set_timing", "ivf_get_stage_ms",
@@ -98,6 +98,7 @@ def load_library() -> C.CDLL:
     lib.ivf_worker_set_device_budget.argtypes = [vp, i64]
     lib.ivf_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.ivf_search_queued.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp, vp]
+    lib.ivf_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.ivf_last_error.restype = C.c_char_p
     lib.ivf_get_info.argtypes = [vp, C.POINTER(Info)]
     lib.ivf_debug_last_probes.argtypes = [vp, vp, vp]
@@ -256,6 +257,16 @@ class Index:
         ev = None if queries_ready is None else queries_ready.cuda_event
         _check(self._lib.ivf_search_queued(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
                                            _ptr(out_scores), _stream_handle(stream), ev))
+        return out_ids, out_scores
+
+    def search_noalloc(self, queries, nprobe: int, k: int, out_ids, out_scores, stream=None):
+        """ivf_search_noalloc: the caller passes every buffer; the library allocates nothing."""
+        import torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        nq = queries.shape[0]
+        assert tuple(out_ids.shape) == (nq, k) and tuple(out_scores.shape) == (nq, k)
+        _check(self._lib.ivf_search_noalloc(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
+                                            _ptr(out_scores), _stream_handle(stream)))
         return out_ids, out_scores
 
     def search_raw(self, queries_ptr, nq, nprobe, k, out_ids_ptr, out_scores_ptr, stream_ptr=None) -> int:

@@ -77,7 +77,7 @@ def test_c1_pq_other_shapes_and_pruning(c1pq, k, nprobe, nq):
         idx.set_option("scan_prune", 1)
 
 
-def test_c1_pq_placement_and_queued_searches_give_the_same_rows(c1pq):
+def test_c1_pq_placement_queued_and_noalloc_give_the_same_rows(c1pq):
     import torch
     w, h, cb, idx = c1pq
     q = W.queries(w, batch=3, nq=24)
@@ -101,8 +101,11 @@ def test_c1_pq_placement_and_queued_searches_give_the_same_rows(c1pq):
     idx.set_option("queue_min_mb", 0)
     st = torch.cuda.Stream()
     outs = [idx.search_queued(qd, w.nprobe, w.k, stream=st) for _ in range(7)]
+    oi = torch.empty((24, w.k), dtype=torch.int64, device="cuda")
+    os_ = torch.empty((24, w.k), dtype=torch.float32, device="cuda")
+    idx.search_noalloc(qd, w.nprobe, w.k, oi, os_, stream=st)
     torch.cuda.synchronize()
-    for ids, sc in outs:
+    for ids, sc in outs + [(oi, os_)]:
         assert np.array_equal(ids.cpu().numpy(), ref[0]) and np.array_equal(sc.cpu().numpy(), ref[1])
     idx.set_option("queue_min_mb", 256)
 
