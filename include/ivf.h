@@ -249,7 +249,8 @@ int ivf_search_queued(ivf_index *idx, const float *queries, int64_t nq, int npro
  *     segments) and in the staged host-list mode ("host_direct" = 0: staging buffers);
  *     host-resident lists read in place are fine.
  *   - The array is shared by every index on the GPU and keeps the last call's contents
- *     (what must start at zero is cleared by the search itself).  Calls issued one after
+ *     (what must start at zero is cleared by the search itself); two calls that overlapped
+ *     on one GPU would race on it.  Calls issued one after
  *     the other are ordered on the device by the library, whatever their streams and
  *     indexes; calls that overlap on one GPU from several host threads are serialised by
  *     a lock while they are issued, but the introspection calls (ivf_debug_last_*,
