@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per k_scan launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE, both
 # scaled against the library's plain copy kernel), and the summary each comes from.
 # Workloads that have not been counted report null.
-TRAFFIC_BYTES = {"C5": 1.66729e7 * 2.000 * 1024 + 5507.56 * 1024,
+TRAFFIC_BYTES = {"C5": 1.66754e7 * 2.000 * 1024 + 8283.61 * 1024,
                  "C5-int8": 8.38722e6 * 2.000 * 1024 + 5468.62 * 1024}
 TRAFFIC_SOURCE = {"C5": "profiles/k_scan_C5_pmc_traffic.md",
                   "C5-int8": "profiles/k_scan_C5_int8_trace_and_traffic.md"}
@@ -161,14 +161,14 @@ def pinned_h2d_rate():
     return 4 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None):
+def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None, tight=False):
     """All timing definitions for one workload on an index that is already placed.
     Returns (report dict, query batches on host and device, first batch's results, output buffers)."""
     import numpy as np
     import torch
     from paper_2504_15302_amd import workloads as W
 
-    q_host = [W.queries(w, batch=b, components=components) for b in range(nb)]
+    q_host = [W.queries(w, batch=b, components=components, tight=tight) for b in range(nb)]
     q_dev = [torch.from_numpy(q).cuda() for q in q_host]
     out_ids = torch.empty((w.nq, w.k), dtype=torch.int64, device="cuda")
     out_scores = torch.empty((w.nq, w.k), dtype=torch.float32, device="cuda")
@@ -219,6 +219,7 @@ def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None
     torch.cuda.synchronize()
     ms_plain = (time.perf_counter() - t0) / steps * 1e3
     plain_scan_ms = float(np.mean([idx.stage_ms(b)["scan"] for b in range(kept)]))
+    plain_stream_ms = float(np.mean([idx.stage_ms(b)["stream"] for b in range(kept)]))
 
     # one search at a time, each synchronised: median
     singles = []
@@ -252,6 +253,7 @@ def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None
         "scan_bytes_per_batch": int(stats[0].scan_bytes),
         "scan_bytes_streamed_per_batch": int(stats[0].scan_bytes_streamed),
         "_stream_ms": float(np.mean(stream_ms)),
+        "_plain_stream_ms": plain_stream_ms,
         "_streamed": float(np.mean([stats[(steps - 1 - b) % nb].scan_bytes_streamed for b in range(kept)])),
     }
     if stages:
@@ -276,9 +278,12 @@ def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None
 
 def pcie_report(rep, direct, h2d):
     streamed = rep["_streamed"]
-    t_stream = rep["scan"]["ms_per_launch"] if direct else rep["_stream_ms"]   # direct reads happen inside the scan
+    # direct reads happen inside the scan; staged copies are a stage of their own (searches
+    # of the staged mode always run on one stream: the figure of the plain-search region)
+    t_stream = rep["scan"]["ms_per_launch"] if direct else rep["_plain_stream_ms"]
     rate = streamed / 1e9 / (t_stream * 1e-3) if t_stream > 0 else None
     return {"streamed_GB_per_batch": streamed / 1e9, "GBps_over_stream_stage": rate,
+            "stream_stage_ms": t_stream,
             "mode": "scan reads pinned host memory directly" if direct else "hipMemcpyAsync to staging on a side stream",
             "pinned_h2d_copy_GBps_1GiB": h2d, "frac_of_h2d_copy": rate / h2d if rate else None}
 
@@ -324,6 +329,9 @@ def main():
     ap.add_argument("--skew-components", type=int, default=0,
                     help="draw every query batch from this many mixture components only (about nq/m queries "
                          "then probe the same lists); 0 = the benchmark's uniform batches")
+    ap.add_argument("--skew-tight", action="store_true",
+                    help="with --skew-components: the queries of a component are near copies of one another, "
+                         "so that all their probed lists are shared, not only the home list")
     ap.add_argument("--read-ceiling-gib", type=int, default=24,
                     help="size of the plain streaming-read measurement (0 skips it)")
     args = ap.parse_args()
@@ -390,13 +398,15 @@ def main():
         torch.cuda.empty_cache()
 
     rep, q_host, q_dev, first, (out_ids, out_scores) = measure(idx, w, args.steps, args.warmup, nb, direct,
-                                                               components=args.skew_components or None)
+                                                               components=args.skew_components or None,
+                                                               tight=args.skew_tight)
     sc = rep["scan"]
     result = {
         "metric": "queries/sec and list-scan HBM GB/s (% of peak), batched IVF top-k search",
         "value": rep["queries_per_s"], "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 accumulate over " + {"fp32": "f32", "fp16": "f16", "int8": "i8 codes + f32 scale"}[w.storage] + " storage",
+        "dtype": "f32 accumulate over " + {"fp32": "f32", "fp16": "f16", "int8": "i8 codes + f32 scale",
+                                           "pq8": "product-quantisation codes (u8) with f32 tables over"}[w.storage] + " storage",
         "data": "synthetic (seeded Gaussian mixture, generated on the GPU; random-init, no dataset)",
         "config": {"workload": workload_label(w),
                    "query_batches_rotated": nb,
@@ -406,9 +416,10 @@ def main():
                    "pairs_per_batch": rep["pairs_per_batch"],
                    "queries_per_probed_list": rep["queries_per_probed_list"],
                    "scan_requested_bytes_per_batch": rep["scan_requested_bytes_per_batch"],
-                   "skew_components": args.skew_components or None,
+                   "skew_components": args.skew_components or None, "skew_tight": bool(args.skew_tight),
                    "step": "one ivf_search_queued call; K calls issued back to back, one synchronisation at the end"},
-        "roofline": {"bound": "hbm", "kernel": "k_scan (scan of HBM-resident probed lists)",
+        "roofline": {"bound": "hbm", "kernel": "k_pq_tables + k_pq_scan (LDS-gather-bound: the HBM figure is context only)"
+                     if w.storage == "pq8" else "k_scan / k_scan_split (scan of the probed lists)",
                      "achieved": sc["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": sc["GBps"] / HBM_PEAK_GBS,
                      "traffic": TRAFFIC_BYTES.get(w.name) if not experiment else None,

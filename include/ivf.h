@@ -130,11 +130,14 @@ int ivf_index_upload_end(ivf_index *idx);
  *   1 (default)  the scan kernel reads them in place from pinned host memory, in the same
  *                launch as the HBM-resident lists (measured ~56 GB/s, 97 % of the box's
  *                pinned host-to-device copy rate);
- *   0            they are copied with hipMemcpyAsync on a side stream into a ring of
+ *   0            they are copied with hipMemcpyAsync on side streams into a ring of
  *                staging buffers ("stage_mb", "nstage"), neighbouring lists merged into
- *                one copy, and each chunk is scanned on the caller's stream as soon as its
- *                event fires, while the resident lists are scanned meanwhile (measured
- *                36-43 GB/s: one copy call per ~2 MB list dominates).
+ *                one copy, the copies of a chunk spread over "nside" copy streams (a copy
+ *                of one ~2 MB list is too short to reach the link's rate by itself), and
+ *                each chunk is scanned on the caller's stream as soon as its events fire,
+ *                while the resident lists are scanned meanwhile (measured 54 GB/s, 94 % of
+ *                the copy rate, with four copy streams; 42 GB/s with one).  This is the
+ *                fallback for systems where device kernels cannot read host memory.
  * INT64_MAX (or anything at least the index size) makes everything resident again.
  * Results of ivf_search do not depend on the budget or on the mode.
  *
@@ -222,10 +225,11 @@ int ivf_search(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int
  *                  once the caller has synchronised it, and work the caller queued on it
  *                  before the call (say, a copy out of out_ids) precedes the writes to
  *                  out_ids / out_scores.
- * While a budget change is under way, in the staged host-list mode, with timing level 1,
- * and when the lists to scan are bounded by less than "queue_min_mb" MiB (default 256:
- * the overlap cannot repay a dozen extra stream and event calls) the search runs exactly
- * like ivf_search, behind queries_ready.  Everything else is as for ivf_search: same
+ * While a budget change is under way, while any list is host-resident (the scan is then
+ * bound by PCIe and nothing is gained), with timing level 1, on a capturing stream, and
+ * when the lists to scan are bounded by less than "queue_min_mb" MiB (default 256: the
+ * overlap cannot repay a dozen extra stream and event calls) the search runs exactly like
+ * ivf_search, behind queries_ready.  Everything else is as for ivf_search: same
  * limits, same scratch growth on first use (of each of the three sets).  Pass a stream
  * of your own rather than the legacy default stream (NULL), whose implicit
  * synchronisation with other streams costs most of the overlap.

@@ -121,7 +121,7 @@ int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offloa
         s.cap_zero_q = qcap;
     }
     if (x->nlist > s.cap_nlist) {
-        if ((rc = dalloc(s.wg_totals, kScanVals * (((size_t)x->nlist + kScanThreads - 1) / kScanThreads), s.bytes))) return rc;
+        if ((rc = dalloc(s.wg_totals, kScanVals * (((size_t)x->nlist + kScanThreadsShared - 1) / kScanThreadsShared), s.bytes))) return rc;
         if ((rc = dalloc(s.pair_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.sblk_start, (size_t)x->nlist, s.bytes))) return rc;
         if ((rc = dalloc(s.item_start, (size_t)x->nlist, s.bytes))) return rc;
@@ -185,7 +185,7 @@ size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, siz
     };
     const size_t o_S = take(4 * (size_t)nq * nlist), o_tmax = take(4 * (size_t)nq * ntile);
     const size_t o_zero = take(4 * (2 * nlist + 16 + 2 * kNumCounters + 2 * (size_t)nq));
-    const size_t o_wg = take(4 * kScanVals * ((nlist + kScanThreads - 1) / kScanThreads));
+    const size_t o_wg = take(4 * kScanVals * ((nlist + kScanThreadsShared - 1) / kScanThreadsShared));
     const size_t o_ps = take(4 * nlist), o_sb = take(4 * nlist), o_is = take(4 * nlist);
     const size_t o_pr = take(4 * npairs), o_pf = take(4 * npairs), o_pp = take(4 * npairs);
     const size_t o_it = take(sizeof(ScanItem) * nblocks), o_sc = take(4 * nblocks * kLanes), o_bm = take(4 * nblocks);
@@ -551,9 +551,10 @@ void enqueue_coarse(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st
 
 // The selection kernels are chains of barriers and dependent loads: with little to select
 // from, a workgroup of 4 wavefronts gets through them faster than one of 16.
-void enqueue_probe_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
+void enqueue_probe_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st, bool under_a_scan) {
     int* hist = s.zeroed;
-    const bool small_probe = x->opt_sel_threads ? x->opt_sel_threads == 256 : c.ntile <= 128;
+    // (under another search's scan only a workgroup of four wavefronts finds room on a compute unit)
+    const bool small_probe = x->opt_sel_threads ? x->opt_sel_threads == 256 : (under_a_scan || c.ntile <= 128);
     if (small_probe)
         hipLaunchKernelGGL((k_probe_select<256>), dim3((unsigned)c.nq), dim3(256), 0, st, s.S, s.tmax, c.nlist, c.ntile, c.nprobe,
                            s.probes, hist);
@@ -572,16 +573,29 @@ void enqueue_regroup(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t s
     // times that size.
     const int fuse = under_a_scan ? 4 : 1;
     if (x->opt_regroup_fused && nlist <= fuse * kFusedMaxLists && npairs <= fuse * kFusedMaxPairs) {
-        // few lists and pairs: one workgroup does the whole regrouping in one launch
-        hipLaunchKernelGGL(k_regroup_small, dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
-                           nlist, nprobe, x->block_bytes, s.probes, npairs, cursor, s.pair_start, s.sblk_start,
-                           s.item_start, s.pair_flat, s.pair_of_probe, s.items, x->d_hits, s.counters);
+        // few lists and pairs: one workgroup does the whole regrouping in one launch (sixteen
+        // wavefronts also under a scan: with four, each thread's share of the lists is a chain
+        // of loads four times as long, and under a scan every link of it is slow — 250 us
+        // against 110 at 4096 lists)
+        hipLaunchKernelGGL((k_regroup_small<kScanThreads>), dim3(1), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len,
+                           x->d_list_ptr, nlist, nprobe, x->block_bytes, s.probes, npairs, cursor, s.pair_start,
+                           s.sblk_start, s.item_start, s.pair_flat, s.pair_of_probe, s.items, x->d_hits, s.counters);
     } else {
-        const unsigned wgs = (unsigned)((nlist + kScanThreads - 1) / kScanThreads);
-        hipLaunchKernelGGL(k_list_partial, dim3(wgs), dim3(kScanThreads), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
-                           nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
-        hipLaunchKernelGGL(k_list_finish, dim3(wgs), dim3(kScanThreads), 0, st, hist, nlist, (int)wgs, s.wg_totals,
-                           s.pair_start, s.sblk_start, s.item_start);
+        if (under_a_scan) {
+            constexpr int T = kScanThreadsShared;
+            const unsigned wgs = (unsigned)((nlist + T - 1) / T);
+            hipLaunchKernelGGL((k_list_partial<T>), dim3(wgs), dim3(T), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                               nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
+            hipLaunchKernelGGL((k_list_finish<T>), dim3(wgs), dim3(T), 0, st, hist, nlist, (int)wgs, s.wg_totals,
+                               s.pair_start, s.sblk_start, s.item_start);
+        } else {
+            constexpr int T = kScanThreads;
+            const unsigned wgs = (unsigned)((nlist + T - 1) / T);
+            hipLaunchKernelGGL((k_list_partial<T>), dim3(wgs), dim3(T), 0, st, hist, x->d_nblk, x->d_len, x->d_list_ptr,
+                               nlist, s.pair_start, s.sblk_start, s.item_start, s.wg_totals, s.counters);
+            hipLaunchKernelGGL((k_list_finish<T>), dim3(wgs), dim3(T), 0, st, hist, nlist, (int)wgs, s.wg_totals,
+                               s.pair_start, s.sblk_start, s.item_start);
+        }
         hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, st, s.probes, npairs,
                            s.pair_start, cursor, s.pair_flat);
         hipLaunchKernelGGL(k_plan, dim3((unsigned)((nlist + 255) / 256)), dim3(256), 0, st, hist, x->d_nblk, x->d_len,
@@ -619,8 +633,8 @@ void enqueue_scan_kernels(ivf_index* x, Scratch& s, const SearchCtx& c, hipStrea
     }
 }
 
-void enqueue_final_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
-    const bool small_final = x->opt_sel_threads ? x->opt_sel_threads == 256 : block_bound(x, 1, c.nprobe) <= 128;
+void enqueue_final_select(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st, bool under_a_scan) {
+    const bool small_final = x->opt_sel_threads ? x->opt_sel_threads == 256 : (under_a_scan || block_bound(x, 1, c.nprobe) <= 128);
     ListTable lt{x->d_len, x->d_nblk, x->d_offsets};
     if (small_final)
         hipLaunchKernelGGL((k_final_select<256>), dim3((unsigned)c.nq), dim3(256), 0, st, s.probes, s.pair_of_probe,
@@ -655,7 +669,7 @@ int search_serial(ivf_index* x, Scratch& s, SearchCtx& c, hipStream_t st) {
     mark();   // 0
     enqueue_coarse(x, s, c, st);
     mark();   // 1
-    enqueue_probe_select(x, s, c, st);
+    enqueue_probe_select(x, s, c, st, false);
     mark();   // 2
     if (c.offload) {
         HIP_TRY(hipMemcpyAsync(s.h_probes, s.probes, sizeof(int32_t) * (size_t)c.npairs, hipMemcpyDeviceToHost, st));
@@ -671,7 +685,7 @@ int search_serial(ivf_index* x, Scratch& s, SearchCtx& c, hipStream_t st) {
         if ((rc = stream_host_lists(x, s, c, st))) return rc;
     }
     mark();   // 5
-    enqueue_final_select(x, s, c, st);
+    enqueue_final_select(x, s, c, st, false);
     mark();   // 6
     HIP_TRY(hipGetLastError());
     if (c.offload) {
@@ -1126,7 +1140,11 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
     // cannot repay the dozen extra stream and event calls it takes.
     const uint64_t bound_bytes = (uint64_t)block_bound(x, c.nq, c.nprobe) * x->block_bytes;
     const bool tiny = bound_bytes < ((uint64_t)x->opt_queue_min_mb << 20);
-    const bool serial = tiny || stream_is_capturing(st) || moves_active(x) || (x->resident_lists < x->nlist && !x->opt_host_direct) || x->timing == 1;
+    // And so does any search over an index with host-resident lists: its scan is bound by
+    // PCIe, there is nothing to gain, and under a scan whose wavefronts sit on PCIe reads
+    // for milliseconds the final selection of the search before would wait that long for
+    // room on a compute unit (8 ms at C4), i.e. its results would be late.
+    const bool serial = tiny || stream_is_capturing(st) || moves_active(x) || x->resident_lists < x->nlist || x->timing == 1;
     const int p = serial ? 0 : x->next_set;
     // Under a scan the front kernels (chains of dependent loads) run several times slower
     // than alone.  Behind a short scan (a few hundred microseconds) one search's worth of
@@ -1162,7 +1180,7 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
     search_set_pruning(x, c);
     if (ready) HIP_TRY(hipStreamWaitEvent(front, ready, 0));
     enqueue_coarse(x, s, c, front);
-    enqueue_probe_select(x, s, c, front);
+    enqueue_probe_select(x, s, c, front, true);
     enqueue_regroup(x, s, c, front, true);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(x->ev_front[p], front));
@@ -1175,7 +1193,7 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
     enqueue_scan(x, s, c, scan);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamWaitEvent(st, scan_done, 0));
-    enqueue_final_select(x, s, c, st);
+    enqueue_final_select(x, s, c, st, true);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s.end, st));
     s.end_recorded = true;

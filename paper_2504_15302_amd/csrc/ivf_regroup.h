@@ -22,7 +22,9 @@ enum {                 // 64-bit counters accumulated by k_list_partial (zero on
     kNumCounters = 8
 };
 
-constexpr int kScanThreads = 1024;
+constexpr int kScanThreads = 1024;   // lists per workgroup of the prefix kernels when they have the GPU to themselves
+constexpr int kScanThreadsShared = 256;   // ... and under another search's scan: a workgroup of sixteen wavefronts finds
+                                          // no room on a compute unit until the scan's grid has drained, one of four does
 constexpr int kHistTopShift = 20;                         // hist[l] = probes + (times best probe << 20)
 constexpr int kHistCountMask = (1 << kHistTopShift) - 1;
 constexpr int kScanVals = 4;   // pairs, score blocks, items of "first" lists, items of the other lists
@@ -32,15 +34,16 @@ constexpr int kScanVals = 4;   // pairs, score blocks, items of "first" lists, i
 // the totals of the workgroups before it.  Scan items are numbered in two classes: lists
 // that are some query's best probe come first, so that the scan meets every query's most
 // promising list early and its bound on the k-th best score is tight almost from the start.
-__global__ __launch_bounds__(kScanThreads) void k_list_partial(
+template <int T>
+__global__ __launch_bounds__(T) void k_list_partial(
     const int* __restrict__ hist, const int32_t* __restrict__ nblk, const int32_t* __restrict__ len,
     const void* const* __restrict__ list_ptr, int nlist, uint32_t* __restrict__ pair_start,
     uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start,
     uint32_t* __restrict__ wg_totals, unsigned long long* __restrict__ counters) {
-    __shared__ uint32_t wsum[kScanThreads / 64][kScanVals];
+    __shared__ uint32_t wsum[T / 64][kScanVals];
     __shared__ unsigned long long extra[3];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int l = blockIdx.x * kScanThreads + t;
+    const int l = blockIdx.x * T + t;
     uint32_t v[kScanVals] = {0, 0, 0, 0};
     unsigned long long uniq = 0, vec = 0, vres = 0;
     bool first = false;
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
         atomicAdd(&extra[2], vres);
     }
     uint32_t base[kScanVals] = {0, 0, 0, 0}, total[kScanVals] = {0, 0, 0, 0};
-    for (int w = 0; w < kScanThreads / 64; ++w)
+    for (int w = 0; w < T / 64; ++w)
 #pragma unroll
         for (int c = 0; c < kScanVals; ++c) {
             uint32_t x = wsum[w][c];
@@ -107,15 +110,16 @@ __global__ __launch_bounds__(kScanThreads) void k_list_partial(
     }
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_list_finish(
+template <int T>
+__global__ __launch_bounds__(T) void k_list_finish(
     const int* __restrict__ hist, int nlist, int nwg, const uint32_t* __restrict__ wg_totals,
     uint32_t* __restrict__ pair_start, uint32_t* __restrict__ sblk_start,
     uint32_t* __restrict__ item_start) {
-    __shared__ uint32_t red[kScanThreads / 64][kScanVals + 1];
+    __shared__ uint32_t red[T / 64][kScanVals + 1];
     __shared__ uint32_t base[kScanVals + 1];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     uint32_t s[kScanVals + 1] = {0, 0, 0, 0, 0};      // [4] = items of "first" lists, all workgroups
-    for (int w = t; w < nwg; w += kScanThreads) {
+    for (int w = t; w < nwg; w += T) {
         if (w < (int)blockIdx.x)
 #pragma unroll
             for (int c = 0; c < kScanVals; ++c) s[c] += wg_totals[w * kScanVals + c];
@@ -130,11 +134,11 @@ __global__ __launch_bounds__(kScanThreads) void k_list_finish(
     __syncthreads();
     if (t <= kScanVals) {
         uint32_t x = 0;
-        for (int w = 0; w < kScanThreads / 64; ++w) x += red[w][t];
+        for (int w = 0; w < T / 64; ++w) x += red[w][t];
         base[t] = x;
     }
     __syncthreads();
-    const int l = blockIdx.x * kScanThreads + t;
+    const int l = blockIdx.x * T + t;
     if (l < nlist) {
         const bool first = ((unsigned)hist[l] >> kHistTopShift) != 0;
         pair_start[l] += base[0];
@@ -210,14 +214,15 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
 // k_list_finish, the same segments as k_pair_fill, the same items as k_plan, with
 // workgroup barriers where the separate kernels have launch boundaries.
 constexpr int kFusedMaxLists = 1024, kFusedMaxPairs = 2048;
-__global__ __launch_bounds__(kScanThreads) void k_regroup_small(
+template <int T>
+__global__ __launch_bounds__(T) void k_regroup_small(
     const int* __restrict__ hist, const int32_t* __restrict__ nblk, const int32_t* __restrict__ len,
     const void* const* __restrict__ list_ptr, int nlist, int nprobe, size_t block_bytes,
     const int32_t* __restrict__ probes, int npairs, int* __restrict__ cursor,
     uint32_t* __restrict__ pair_start, uint32_t* __restrict__ sblk_start, uint32_t* __restrict__ item_start,
     uint32_t* __restrict__ pair_flat, uint32_t* __restrict__ pair_of_probe, ScanItem* __restrict__ items,
     uint32_t* __restrict__ hits, unsigned long long* __restrict__ counters) {
-    __shared__ uint32_t wsum[kScanThreads / 64][kScanVals];
+    __shared__ uint32_t wsum[T / 64][kScanVals];
     __shared__ uint32_t run[kScanVals];              // totals of the chunks done so far
     __shared__ unsigned long long extra[3];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -225,7 +230,7 @@ __global__ __launch_bounds__(kScanThreads) void k_regroup_small(
     if (t < 3) extra[t] = 0;
     __syncthreads();
     // 1. exclusive prefix sums over the lists (the loop runs once for up to 1024 lists)
-    for (int c0 = 0; c0 < nlist; c0 += kScanThreads) {
+    for (int c0 = 0; c0 < nlist; c0 += T) {
         const int l = c0 + t;
         uint32_t v[kScanVals] = {0, 0, 0, 0};
         unsigned long long uniq = 0, vec = 0, vres = 0;
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(kScanThreads) void k_regroup_small(
         uint32_t base[kScanVals], total[kScanVals];
 #pragma unroll
         for (int c = 0; c < kScanVals; ++c) { base[c] = run[c]; total[c] = 0; }
-        for (int w = 0; w < kScanThreads / 64; ++w)
+        for (int w = 0; w < T / 64; ++w)
 #pragma unroll
             for (int c = 0; c < kScanVals; ++c) {
                 uint32_t x = wsum[w][c];
@@ -293,14 +298,14 @@ __global__ __launch_bounds__(kScanThreads) void k_regroup_small(
     }
     const uint32_t first_items = run[2];             // items of the other lists come after these
     // 2. every (query, probe) pair drops into its list's segment
-    for (int f = t; f < npairs; f += kScanThreads) {
+    for (int f = t; f < npairs; f += T) {
         const int l = probes[f];
         const int slot = atomicAdd(&cursor[l], 1);
         pair_flat[pair_start[l] + slot] = (uint32_t)f;
     }
     __syncthreads();
     // 3. per list: order the segment by query, fill the pair table, write the scan items
-    for (int l = t; l < nlist; l += kScanThreads) {
+    for (int l = t; l < nlist; l += T) {
         const unsigned h = (unsigned)hist[l];
         const unsigned cnt = h & kHistCountMask;
         if (!cnt) continue;

@@ -127,11 +127,14 @@ def list_offsets(w: Workload) -> np.ndarray:
     return off
 
 
-def queries(w: Workload, batch: int = 0, nq: Optional[int] = None, components: Optional[int] = None) -> np.ndarray:
+def queries(w: Workload, batch: int = 0, nq: Optional[int] = None, components: Optional[int] = None,
+            tight: bool = False) -> np.ndarray:
     """[nq, d] float32 unit query embeddings of batch number `batch`.  The first
     rows of a batch do not depend on nq, so C4's 8 queries are C3's first 8.
     With `components` = m the batch is skewed: its queries come from only m mixture
-    components (drawn per batch), so about nq/m queries probe the same lists."""
+    components (drawn per batch), so about nq/m queries probe the same home list; with
+    `tight` the queries of a component are near copies of one another (the component's
+    first query plus a thousandth of the noise), so they probe the same lists throughout."""
     nq = w.nq if nq is None else nq
     cen = centroids(w)
     out = np.empty((nq, w.d), dtype=np.float32)
@@ -143,6 +146,12 @@ def queries(w: Workload, batch: int = 0, nq: Optional[int] = None, components: O
         comp = int(rng.integers(0, w.nlist))
         if hot is not None:
             comp = int(hot[comp % components])
+        if hot is not None and tight:
+            g0 = np.random.default_rng([w.seed, _STREAM_QUERY, batch, (1 << 21) + comp]).standard_normal(w.d).astype(np.float32)
+            g = g0 + np.float32(1e-3) * rng.standard_normal(w.d).astype(np.float32)
+            x = cen[comp] + np.float32(w.sigma) * g
+            out[i] = x / np.linalg.norm(x)
+            continue
         g = rng.standard_normal(w.d).astype(np.float32)
         x = cen[comp] + np.float32(w.sigma) * g
         out[i] = x / np.linalg.norm(x)

@@ -185,6 +185,13 @@ def test_skewed_batch_sixteen_queries_per_list(c1):
     sub = q[::16]
     one = gpu_search(idx, sub, w.nprobe, w.k)
     assert np.array_equal(one[0], got[0][::16]) and np.array_equal(one[1], got[1][::16])
+    # near copies of 8 queries: every probed list is shared by about 16 queries
+    q = W.queries(w, batch=9, nq=128, components=8, tight=True)
+    say("C1 skewed, tight: every probed list shared by ~16 queries")
+    got = gpu_search(idx, q, w.nprobe, w.k)
+    check_against_oracle(h.centroids, h.vectors, h.ids, h.offsets, q, w.nprobe, w.k, got, w.storage)
+    st = idx.last_search_stats()
+    assert st.pairs / st.unique_lists >= 10
 
 
 @pytest.mark.parametrize("nq", [33, 64, 65, 129, 300])

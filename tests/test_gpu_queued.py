@@ -130,8 +130,8 @@ def test_consecutive_searches_of_one_index_on_different_streams(c1):
 
 
 def test_queued_searches_through_budget_changes_and_placements(c1):
-    """Host-resident lists read in place keep the overlapped path; a background budget change
-    and the staged mode fall back to one stream; rows never change."""
+    """With host-resident lists, during a background budget change and in the staged mode
+    queued searches run on one stream; rows never change."""
     import torch
     w, h, idx = c1
     qs, qd, refs = _refs(idx, w, 3)
