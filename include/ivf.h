@@ -215,7 +215,17 @@ int ivf_search(ivf_index *idx, const float *queries, int64_t nq, int nprobe, int
  * selection and regrouping of search i+1 run under the list scan of search i, and the
  * final selection of search i (on the caller's stream) under the scan of search i+1.  The
  * library uses three streams of its own (two for the front stages, one for the scans) and
- * three sets of scratch memory taken in turn.
+ * three sets of scratch memory taken in turn.  A process has four hardware queues, and
+ * streams that share one run one after the other whatever their events say, so the three
+ * must sit on queues other than the caller's and each other's; HIP does not tell which
+ * queue a stream got.  The first queued search of an index that finds `stream` idle
+ * therefore tries it out (once per index, a few milliseconds, with a device-wide
+ * synchronisation): it makes streams one by one, runs a 60 us kernel on one stream and
+ * an empty one on the other, keeps a stream if the empty kernel ends first against the
+ * caller's stream and every stream kept so far, and destroys the others.  A caller that
+ * changes streams later keeps that choice.  The library makes its streams when they are
+ * first needed (these three, the copy streams of the staged mode, those of a budget
+ * change), so an index that never uses a feature adds no stream to the process.
  *   queries_ready  hipEvent_t after which `queries` may be read, or NULL if it may be
  *                  read as soon as the call is made.  Unlike ivf_search, the call does NOT
  *                  order its reading of `queries` behind earlier work on `stream`: that

@@ -336,6 +336,10 @@ int stream_host_lists(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t 
     const int nprobe = c.nprobe;
     HIP_TRY(hipEventSynchronize(x->ev_probes));
     const int nside = (int)std::min<int64_t>(kMaxSide, std::max<int64_t>(1, x->opt_nside));
+    for (int i = 0; i < kMaxSide; ++i) {
+        int rc = need_stream(x->side[i]);
+        if (rc) return rc;
+    }
     for (int i = 0; i < kMaxSide; ++i) HIP_TRY(hipStreamSynchronize(x->side[i]));   // pinned item mirror of the previous search is free
     const size_t npairs = (size_t)nq * nprobe;
     std::vector<std::pair<int32_t, uint32_t>> pl(npairs);
@@ -724,11 +728,9 @@ int ivf_index_create(ivf_index** out) {
     hipError_t e = hipGetDevice(&x->device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, x->device);
-    for (int i = 0; e == hipSuccess && i < kMaxSide; ++i) e = hipStreamCreateWithFlags(&x->side[i], hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->move_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->patch_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipStreamCreateWithFlags(&x->pipe_scan, hipStreamNonBlocking);
-    for (int i = 0; e == hipSuccess && i < 2; ++i) e = hipStreamCreateWithFlags(&x->pipe_front[i], hipStreamNonBlocking);
+    // The library's own streams are made when first needed (need_stream): a process has
+    // four hardware queues, streams that share one run one after the other, and which
+    // streams share depends on how many exist.
     for (int i = 0; e == hipSuccess && i < kSets; ++i) {
         e = hipEventCreateWithFlags(&x->ev_front[i], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&x->ev_scan[i], hipEventDisableTiming);
@@ -774,6 +776,8 @@ void ivf_index_destroy(ivf_index* x) {
     if (x->move_stream) (void)hipStreamDestroy(x->move_stream);
     if (x->patch_stream) (void)hipStreamDestroy(x->patch_stream);
     if (x->pipe_scan) (void)hipStreamDestroy(x->pipe_scan);
+    for (int i = 0; i < 2; ++i)
+        if (x->ev_trial[i]) (void)hipEventDestroy(x->ev_trial[i]);
     for (int i = 0; i < 2; ++i)
         if (x->pipe_front[i]) (void)hipStreamDestroy(x->pipe_front[i]);
     for (int i = 0; i < kSets; ++i) {
@@ -1127,6 +1131,89 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     return search_serial(x, s, c, st);
 }
 
+// A single wavefront that runs for about `ticks` periods of the 100 MHz wall clock and then
+// ends; the iteration cap ends it whatever the clock does.
+__global__ void k_spin(long long ticks, unsigned* __restrict__ sink) {
+    const long long t0 = wall_clock64();
+    unsigned n = 0;
+    while (wall_clock64() - t0 < ticks && n < (1u << 24)) ++n;
+    if (n == 0xffffffffu) sink[0] = n;       // never true: keeps the loop
+}
+
+__global__ void k_nothing() {}
+
+// Does a kernel on `b` run while one on `a` is still running?  (Both streams idle.)  A
+// kernel of about 60 us goes to `a`, an empty one to `b`; the streams share a hardware
+// queue if the empty one ends after the long one.
+int streams_run_side_by_side(ivf_index* x, hipStream_t a, hipStream_t b, bool& yes) {
+    hipLaunchKernelGGL(k_spin, dim3(1), dim3(64), 0, a, (long long)6000, (unsigned*)x->h_counters);
+    HIP_TRY(hipEventRecord(x->ev_trial[0], a));
+    hipLaunchKernelGGL(k_nothing, dim3(1), dim3(64), 0, b);
+    HIP_TRY(hipEventRecord(x->ev_trial[1], b));
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventSynchronize(x->ev_trial[0]));
+    HIP_TRY(hipEventSynchronize(x->ev_trial[1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, x->ev_trial[1], x->ev_trial[0]));   // > 0: b's ended first
+    yes = ms > 0.02f;
+    return 0;
+}
+
+// Picks the library's three streams for queued searches (two for front stages, one for the
+// scans) so that they and the caller's stream `st` run side by side, i.e. sit on different
+// hardware queues: new streams are made one by one and tried against the caller's stream
+// and those picked so far; those that share a queue with one of them are destroyed again
+// at the end.  Done once per index, at the first queued search that finds `st` idle (work
+// already on it would make every trial look like a shared queue) or, failing that, at the
+// eighth, which waits for the device; a later call on another stream keeps the choice.
+// When a dozen streams do not yield three, the rest are taken as they come: the searches
+// are then correct and slower.
+int pick_pipe_streams(ivf_index* x, hipStream_t st) {
+    if (x->pipe_picked) return 0;
+    int rc;
+    const bool idle = hipStreamQuery(st) == hipSuccess;
+    (void)hipGetLastError();
+    if (!idle && ++x->pipe_pick_tries < 8) {
+        // not now: make do with streams as they come, and try again at the next search
+        for (hipStream_t* s : {&x->pipe_front[0], &x->pipe_front[1], &x->pipe_scan})
+            if ((rc = need_stream(*s))) return rc;
+        return 0;
+    }
+    for (int i = 0; i < 2; ++i)
+        if (!x->ev_trial[i]) HIP_TRY(hipEventCreate(&x->ev_trial[i]));
+    // earlier searches may still run on streams made before: trials need them idle
+    HIP_TRY(hipDeviceSynchronize());
+    std::vector<hipStream_t> picked, spare;
+    for (hipStream_t s : {x->pipe_front[0], x->pipe_front[1], x->pipe_scan})
+        if (s) spare.push_back(s);               // made by a call that could not run the trials
+    x->pipe_front[0] = x->pipe_front[1] = x->pipe_scan = nullptr;
+    std::vector<hipStream_t> tried;
+    for (int n = 0; n < 12 && picked.size() < 3; ++n) {
+        hipStream_t c = nullptr;
+        if (!spare.empty()) { c = spare.back(); spare.pop_back(); }
+        else if ((rc = need_stream(c))) return rc;
+        bool ok = true;
+        if ((rc = streams_run_side_by_side(x, st, c, ok))) return rc;
+        for (size_t i = 0; ok && i < picked.size(); ++i)
+            if ((rc = streams_run_side_by_side(x, picked[i], c, ok))) return rc;
+        (ok ? picked : tried).push_back(c);
+    }
+    for (hipStream_t s : spare) tried.push_back(s);
+    while (picked.size() < 3) {
+        hipStream_t c = nullptr;
+        if (!tried.empty()) { c = tried.back(); tried.pop_back(); }
+        else if ((rc = need_stream(c))) return rc;
+        picked.push_back(c);
+    }
+    for (hipStream_t s : tried) (void)hipStreamDestroy(s);
+    x->pipe_scan = picked[0];
+    x->pipe_front[0] = picked[1];
+    x->pipe_front[1] = picked[2];
+    x->pipe_picked = true;
+    x->pipe_caller = st;
+    return 0;
+}
+
 int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k, int64_t* out_ids,
                       float* out_scores, void* stream, void* queries_ready) {
     SearchCtx c;
@@ -1151,7 +1238,9 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
     // them no longer fits, and the searches' front stages alternate between two streams;
     // behind a long scan a second stream only takes more from the scan.
     const int fronts = x->opt_queue_fronts ? (int)x->opt_queue_fronts : bound_bytes < ((uint64_t)4 << 30) ? 2 : 1;
-    hipStream_t first = serial ? st : x->pipe_front[x->queued_count % (uint64_t)fronts];
+    if (!serial && (rc = pick_pipe_streams(x, st))) return rc;
+    hipStream_t own_front = x->pipe_front[x->queued_count % (uint64_t)fronts];
+    hipStream_t first = serial ? st : own_front;
     Scratch& s = x->sc[p];
     if ((rc = order_after_last_use(s, st, first))) return rc;
     if (serial) {

@@ -55,6 +55,12 @@ int fail(int code, const char* fmt, ...) {
         }                                                                                  \
     } while (0)
 
+// A stream of the library's own, made at its first use.
+inline int need_stream(hipStream_t& s) {
+    if (!s) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    return 0;
+}
+
 bool is_device_ptr(const void* p) {
     hipPointerAttribute_t a;
     hipError_t e = hipPointerGetAttributes(&a, p);
@@ -223,6 +229,14 @@ struct ivf_index {
     // times slower than alone, and two searches' worth side by side keep up with the scans),
     // its scan on pipe_scan behind the scan before it, its final selection on the caller's stream
     hipStream_t pipe_front[2] = {}, pipe_scan = nullptr;
+    // These three and the caller's stream should sit on four different hardware queues (a
+    // process has four; streams that share one run one after the other, whatever their
+    // events say).  Which queue a stream gets cannot be asked, so the first queued search
+    // finds out by trial which streams run side by side (pick_pipe_streams).
+    bool pipe_picked = false;
+    int pipe_pick_tries = 0;
+    hipStream_t pipe_caller = nullptr;  // the caller's stream that the three were picked against
+    hipEvent_t ev_trial[2] = {};        // timing events of the trials
     uint64_t queued_count = 0;
     hipEvent_t ev_front[kSets] = {}, ev_scan[kSets] = {};
     int next_set = 0;

@@ -298,6 +298,9 @@ int moves_drain(ivf_index* x, bool cancel) {
 // The device is idle and no change is in progress.
 int budget_plan(ivf_index* x, int64_t bytes) {
     const int64_t nlist = x->nlist;
+    int rc_streams = need_stream(x->move_stream);
+    if (!rc_streams) rc_streams = need_stream(x->patch_stream);
+    if (rc_streams) return rc_streams;
     x->moved_h2d = x->moved_d2h = x->moved_d2d = 0;
     x->move_rc = 0;
     x->move_msg.clear();

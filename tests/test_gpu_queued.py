@@ -190,3 +190,36 @@ def test_queued_searches_at_a_larger_shape_with_pruning():
     assert ms["scan"] > 0 and ms["coarse"] == 0
     idx.set_timing(0)
     idx.close()
+
+
+def test_first_queued_searches_on_a_busy_stream():
+    """The library picks its three streams by trial at the first queued search that finds the
+    caller's stream idle; searches before that (here: ten on a stream that still has work)
+    run on streams taken as they come, and after the eighth it stops waiting for an idle
+    moment.  Rows are the same throughout, and the same again once the stream is idle."""
+    import torch
+    w = W.CONFIGS["C1"]
+    h = W.build_host_index(w)
+    say("C1: fresh index, first queued searches behind work on the caller's stream")
+    idx = upload_host_index(h)
+    try:
+        idx.set_option("queue_min_mb", 0)
+        qs, qd, refs = _refs(idx, w, 3)
+        st = torch.cuda.Stream()
+        a = torch.randn((4096, 4096), device="cuda")
+        torch.cuda.synchronize()
+        outs = []
+        with torch.cuda.stream(st):
+            for i in range(10):
+                for _ in range(4):
+                    a @ a                              # a few milliseconds ahead of every search
+                outs.append(idx.search_queued(qd[i % 3], w.nprobe, w.k, stream=st))
+        st.synchronize()
+        for i in range(6):                             # idle now
+            outs.append(idx.search_queued(qd[(10 + i) % 3], w.nprobe, w.k, stream=st))
+        st.synchronize()
+        for i, (ids, sc) in enumerate(outs):
+            assert np.array_equal(ids.cpu().numpy(), refs[i % 3][0]), f"search {i}"
+            assert np.array_equal(sc.cpu().numpy(), refs[i % 3][1]), f"search {i}"
+    finally:
+        idx.close()
