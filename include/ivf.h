@@ -186,7 +186,12 @@ int ivf_budget_wait(ivf_index *idx);
 
 /*
  * ivf_search — batched top-k inner-product search.
- *   queries     [nq, d] fp32 row-major, DEVICE pointer
+ *   queries     [nq, d] fp32 row-major: a DEVICE pointer, or pinned host memory
+ *               (hipHostMalloc).  Pinned queries are first copied to scratch memory on
+ *               the stream of the search's first kernel (for ivf_search_queued that is
+ *               a stream of the library, so the copy does not queue behind the caller's
+ *               stream); they must stay unchanged until the search is done.  Pageable
+ *               host memory is refused (IVF_ERR_INVALID).
  *   nq          batch size (0 is allowed and does nothing)
  *   nprobe      inverted lists scanned per query (the nprobe largest <q, centroid>,
  *               ties to the smaller list number)
@@ -194,6 +199,9 @@ int ivf_budget_wait(ivf_index *idx);
  *   out_ids     [nq, k] int64 DEVICE pointer: user ids, best first; -1 where fewer
  *               than k candidates exist
  *   out_scores  [nq, k] fp32 DEVICE pointer: inner products; -inf where padded
+ *               (both are only written, by the final selection kernel, so pinned host
+ *               memory works as well and saves the copy back: the retrieval worker does
+ *               that)
  *   stream      hipStream_t (NULL = default stream).  Work is enqueued on it; the
  *               outputs are valid once the caller has synchronised it.  The call does
  *               not block once the scratch buffers are large enough, except in the
@@ -257,7 +265,7 @@ int ivf_search_queued(ivf_index *idx, const float *queries, int64_t nq, int npro
  * own copy of that array until the process ends.
  *   - A search that needs more returns IVF_ERR_LIMIT with the size in the message; the
  *     need is about 4*nq*nlist bytes plus 292 bytes per 64-vector block of nq times the
- *     nprobe longest lists (the benchmark's 100k, 2M and 20M-vector configurations fit,
+ *     nprobe longest lists, plus 4*nq*d for queries in pinned host memory (the benchmark's 100k, 2M and 20M-vector configurations fit,
  *     the 100M one with 128 queries does not).
  *   - IVF_ERR_INVALID while a budget change is under way (it allocates and frees pool
  *     segments) and in the staged host-list mode ("host_direct" = 0: staging buffers);

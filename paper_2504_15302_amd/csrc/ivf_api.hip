@@ -47,7 +47,7 @@ void free_scratch(Scratch& s) {
     dfree(s.S); dfree(s.tmax); dfree(s.probes); dfree(s.zeroed); dfree(s.pair_start);
     dfree(s.sblk_start); dfree(s.item_start); dfree(s.wg_totals); dfree(s.pair_flat);
     dfree(s.pair_of_probe); dfree(s.items); dfree(s.stream_items);
-    dfree(s.scores); dfree(s.bmax); dfree(s.pq_tables);
+    dfree(s.scores); dfree(s.bmax); dfree(s.pq_tables); dfree(s.q_stage);
     if (s.h_probes) (void)hipHostFree(s.h_probes);
     if (s.h_items) (void)hipHostFree(s.h_items);
     s = Scratch();
@@ -100,7 +100,7 @@ int64_t block_bound(const ivf_index* x, int64_t nq, int nprobe) {
     return nq * x->top_nblk_prefix[p];
 }
 
-int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offload) {
+int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offload, bool q_host) {
     const int64_t ntile = (x->nlist + kCoarseTile - 1) / kCoarseTile;
     const size_t npairs = (size_t)nq * nprobe;
     const size_t nblocks = (size_t)std::max<int64_t>(1, block_bound(x, nq, nprobe));
@@ -143,6 +143,10 @@ int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offloa
         if ((rc = dalloc(s.pq_tables, (size_t)nq * x->pq_m * 256, s.bytes))) return rc;
         s.cap_pq_q = (size_t)nq;
     }
+    if (q_host && (size_t)nq * x->d > s.cap_q_stage) {
+        if ((rc = dalloc(s.q_stage, (size_t)nq * x->d, s.bytes))) return rc;
+        s.cap_q_stage = (size_t)nq * x->d;
+    }
     if (offload) {
         if (nblocks > s.cap_stream_items) {
             if ((rc = dalloc(s.stream_items, nblocks, s.bytes))) return rc;
@@ -172,7 +176,7 @@ int ensure_scratch(ivf_index* x, Scratch& s, int64_t nq, int nprobe, bool offloa
 
 // The same buffers as slices of one region that the caller owns (256-byte aligned, in a
 // fixed order).  Returns the bytes the search needs; `s` is filled only if they fit in `cap`.
-size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, size_t cap, Scratch& s) {
+size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, bool q_host, char* base, size_t cap, Scratch& s) {
     const size_t nlist = (size_t)x->nlist;
     const size_t ntile = (nlist + kCoarseTile - 1) / kCoarseTile;
     const size_t npairs = (size_t)nq * nprobe;
@@ -190,6 +194,7 @@ size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, siz
     const size_t o_pr = take(4 * npairs), o_pf = take(4 * npairs), o_pp = take(4 * npairs);
     const size_t o_it = take(sizeof(ScanItem) * nblocks), o_sc = take(4 * nblocks * kLanes), o_bm = take(4 * nblocks);
     const size_t o_pq = x->dtype == IVF_PQ8 ? take(4 * (size_t)nq * x->pq_m * 256) : 0;
+    const size_t o_qs = q_host ? take(4 * (size_t)nq * x->d) : 0;
     if (off > cap) return off;
     const hipEvent_t end = s.end;
     const bool end_recorded = s.end_recorded;
@@ -213,6 +218,7 @@ size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, siz
     s.scores = reinterpret_cast<float*>(base + o_sc);
     s.bmax = reinterpret_cast<float*>(base + o_bm);
     if (x->dtype == IVF_PQ8) s.pq_tables = reinterpret_cast<float*>(base + o_pq);
+    if (q_host) s.q_stage = reinterpret_cast<float*>(base + o_qs);
     s.bytes = off;
     return off;
 }
@@ -220,6 +226,7 @@ size_t carve_scratch(const ivf_index* x, int64_t nq, int nprobe, char* base, siz
 // One search as the launch sequence sees it.
 struct SearchCtx {
     const float* Q = nullptr;
+    bool q_host = false;               // Q is pinned host memory: the search starts with a copy to the device
     int64_t nq = 0;
     int nprobe = 0, k = 0;
     int64_t* out_ids = nullptr;
@@ -476,6 +483,15 @@ int search_args(ivf_index* x, const float* queries, int64_t nq, int nprobe, int 
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev != x->device)
         return fail(IVF_ERR_INVALID, "the index lives on HIP device %d but the current device is %d", x->device, dev);
+    hipPointerAttribute_t qa;
+    if (hipPointerGetAttributes(&qa, queries) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(IVF_ERR_INVALID, "queries is neither device memory nor pinned host memory (hipHostMalloc)");
+    }
+    if (qa.type != hipMemoryTypeHost && qa.type != hipMemoryTypeDevice && qa.type != hipMemoryTypeManaged &&
+        qa.type != hipMemoryTypeUnified)
+        return fail(IVF_ERR_INVALID, "queries is neither device memory nor pinned host memory (hipHostMalloc)");
+    c.q_host = qa.type == hipMemoryTypeHost;
     c.Q = queries; c.nq = nq; c.nprobe = nprobe; c.k = k; c.out_ids = out_ids; c.out_scores = out_scores;
     c.nlist = (int)x->nlist;
     c.ntile = (c.nlist + kCoarseTile - 1) / kCoarseTile;
@@ -660,8 +676,18 @@ void search_epilogue(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t s
 }
 
 // The whole search as one chain of kernels on the caller's stream.
+// Queries in pinned host memory: every kernel reads the copy that this puts in front of the
+// search, on the stream of its first kernel (no stream or event of the caller's involved).
+int stage_queries(ivf_index* x, Scratch& s, SearchCtx& c, hipStream_t first) {
+    if (!c.q_host) return 0;
+    HIP_TRY(hipMemcpyAsync(s.q_stage, c.Q, sizeof(float) * (size_t)c.nq * x->d, hipMemcpyHostToDevice, first));
+    c.Q = s.q_stage;
+    return 0;
+}
+
 int search_serial(ivf_index* x, Scratch& s, SearchCtx& c, hipStream_t st) {
     int rc;
+    if ((rc = stage_queries(x, s, c, st))) return rc;
     search_set_pruning(x, c);
     const int tm = x->timing;                  // 0 off, 1 every stage, 2 the scan and streaming stages only
     hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
@@ -1119,7 +1145,7 @@ int ivf_search(ivf_index* x, const float* queries, int64_t nq, int nprobe, int k
     Scratch& s = x->sc[0];
     if ((rc = order_after_last_use(s, st, st))) return rc;
     if ((rc = search_prologue(x, st, c))) return rc;
-    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload))) {
+    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload, c.q_host))) {
         // a failed growth leaves some buffers freed: drop all of them so that the sizes on
         // record match what exists (the next search allocates afresh); the error message stays
         std::string msg = g_err;
@@ -1247,7 +1273,7 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
         if (ready) HIP_TRY(hipStreamWaitEvent(st, ready, 0));
         if ((rc = search_prologue(x, st, c))) return rc;
     }
-    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload))) {
+    if ((rc = ensure_scratch(x, s, c.nq, c.nprobe, c.offload, c.q_host))) {
         std::string msg = g_err;
         (void)hipDeviceSynchronize();
         free_scratch(s);
@@ -1268,6 +1294,7 @@ int ivf_search_queued(ivf_index* x, const float* queries, int64_t nq, int nprobe
     hipEvent_t* evs = x->ev[x->timed_searches % kTimingSlots];
     search_set_pruning(x, c);
     if (ready) HIP_TRY(hipStreamWaitEvent(front, ready, 0));
+    if ((rc = stage_queries(x, s, c, front))) return rc;
     enqueue_coarse(x, s, c, front);
     enqueue_probe_select(x, s, c, front, true);
     enqueue_regroup(x, s, c, front, true);
@@ -1306,7 +1333,7 @@ int ivf_search_noalloc(ivf_index* x, const float* queries, int64_t nq, int nprob
         return fail(IVF_ERR_INVALID, "ivf_search_noalloc: the staged host-list mode needs staging buffers; use host_direct = 1");
     if (!x->static_base) return fail(IVF_ERR_HIP, "ivf_search_noalloc: the static scratch array has no address on this device");
     Scratch& s = x->sc_static;
-    const size_t need = carve_scratch(x, c.nq, c.nprobe, x->static_base, kStaticScratchBytes, s);
+    const size_t need = carve_scratch(x, c.nq, c.nprobe, c.q_host, x->static_base, kStaticScratchBytes, s);
     if (need > kStaticScratchBytes)
         return fail(IVF_ERR_LIMIT, "ivf_search_noalloc: this search needs %zu bytes of scratch, the static array holds %zu "
                     "(nq*nlist coarse scores plus 292 bytes per 64-vector block of nq times the nprobe longest lists)",

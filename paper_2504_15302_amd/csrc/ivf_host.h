@@ -112,6 +112,8 @@ struct Scratch {
     float* scores = nullptr;
     float* bmax = nullptr;
     float* pq_tables = nullptr;     // product-quantised lists: [nq][M][256] inner products with the codewords
+    float* q_stage = nullptr;       // device copy of queries that the caller keeps in pinned host memory
+    size_t cap_q_stage = 0;         // in floats
     size_t cap_pq_q = 0;
     // pinned host mirrors for the streamed path
     int32_t* h_probes = nullptr;

@@ -56,58 +56,44 @@ struct ivf_worker {
 
 namespace {
 
-// One batch on its way through the GPU: its own stream, staging buffers and events, so
-// that the next batch can be issued while this one is still being searched.
+// One batch on its way through the GPU: its own pinned buffers and an event, so that the
+// next batch can be issued while this one is still being searched.  The search reads the
+// queries from the pinned buffer (its first stream copies them to the device, so the copy
+// does not queue behind the batch before on the worker's stream) and its final selection
+// writes the rows straight into the pinned result buffers.  Every batch goes to the one
+// stream of the worker: a process has four hardware queues, the queued search needs three
+// for its own streams, and streams that share a queue run one after the other.
 struct Slot {
-    hipStream_t st = nullptr;
-    hipEvent_t ready = nullptr, done = nullptr;   // queries have landed; results have landed
-    float *hq = nullptr, *dq = nullptr, *hs = nullptr, *ds = nullptr;
-    int64_t *hi = nullptr, *di = nullptr;
+    hipEvent_t done = nullptr;                    // results have landed
+    float *hq = nullptr, *hs = nullptr;
+    int64_t* hi = nullptr;
     std::vector<Request> batch;
     bool busy = false;
     std::chrono::steady_clock::time_point issued;
 };
 
 bool slot_init(Slot& s, size_t B, int d, int k) {
-    return hipStreamCreateWithFlags(&s.st, hipStreamNonBlocking) == hipSuccess &&
-           hipEventCreateWithFlags(&s.ready, hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess &&
+    return hipEventCreateWithFlags(&s.done, hipEventDisableTiming) == hipSuccess &&
            hipHostMalloc(reinterpret_cast<void**>(&s.hq), B * d * sizeof(float)) == hipSuccess &&
            hipHostMalloc(reinterpret_cast<void**>(&s.hs), B * k * sizeof(float)) == hipSuccess &&
-           hipHostMalloc(reinterpret_cast<void**>(&s.hi), B * k * sizeof(int64_t)) == hipSuccess &&
-           hipMalloc(reinterpret_cast<void**>(&s.dq), B * d * sizeof(float)) == hipSuccess &&
-           hipMalloc(reinterpret_cast<void**>(&s.ds), B * k * sizeof(float)) == hipSuccess &&
-           hipMalloc(reinterpret_cast<void**>(&s.di), B * k * sizeof(int64_t)) == hipSuccess;
+           hipHostMalloc(reinterpret_cast<void**>(&s.hi), B * k * sizeof(int64_t)) == hipSuccess;
 }
 
 void slot_free(Slot& s) {
-    if (s.st) { (void)hipStreamSynchronize(s.st); (void)hipStreamDestroy(s.st); }
-    if (s.ready) (void)hipEventDestroy(s.ready);
     if (s.done) (void)hipEventDestroy(s.done);
     if (s.hq) (void)hipHostFree(s.hq);
     if (s.hs) (void)hipHostFree(s.hs);
     if (s.hi) (void)hipHostFree(s.hi);
-    if (s.dq) (void)hipFree(s.dq);
-    if (s.ds) (void)hipFree(s.ds);
-    if (s.di) (void)hipFree(s.di);
 }
 
-// Copies the batch's queries to the device and queues the search and the copies back.
-int slot_issue(ivf_worker* w, Slot& s) {
+// Queues the search of the slot's batch on the worker's stream.
+int slot_issue(ivf_worker* w, Slot& s, hipStream_t st) {
     const size_t nb = s.batch.size();
     for (size_t i = 0; i < nb; ++i) std::memcpy(s.hq + i * w->d, s.batch[i].q.data(), sizeof(float) * w->d);
     s.issued = std::chrono::steady_clock::now();
-    if (hipMemcpyAsync(s.dq, s.hq, nb * w->d * sizeof(float), hipMemcpyHostToDevice, s.st) != hipSuccess ||
-        hipEventRecord(s.ready, s.st) != hipSuccess)
-        return IVF_ERR_HIP;
-    // the search reads the queries behind `ready`, not behind the stream: its front stages
-    // run under the scan of the batch issued before it
-    int rc = ivf_search_queued(w->idx, s.dq, (int64_t)nb, w->nprobe, w->k, s.di, s.ds, s.st, s.ready);
+    int rc = ivf_search_queued(w->idx, s.hq, (int64_t)nb, w->nprobe, w->k, s.hi, s.hs, st, nullptr);
     if (rc) return rc;
-    if (hipMemcpyAsync(s.hi, s.di, nb * w->k * sizeof(int64_t), hipMemcpyDeviceToHost, s.st) != hipSuccess ||
-        hipMemcpyAsync(s.hs, s.ds, nb * w->k * sizeof(float), hipMemcpyDeviceToHost, s.st) != hipSuccess ||
-        hipEventRecord(s.done, s.st) != hipSuccess)
-        return IVF_ERR_HIP;
+    if (hipEventRecord(s.done, st) != hipSuccess) return IVF_ERR_HIP;
     s.busy = true;
     return 0;
 }
@@ -116,7 +102,8 @@ void worker_loop(ivf_worker* w) {
     if (hipSetDevice(w->device) != hipSuccess) { std::lock_guard<std::mutex> g(w->mu); w->failed = true; w->fail_code = IVF_ERR_HIP; w->cv_res.notify_all(); return; }
     constexpr int kSlots = 2;                      // batches in flight
     Slot slots[kSlots];
-    bool ok = true;
+    hipStream_t st = nullptr;
+    bool ok = hipStreamCreateWithFlags(&st, hipStreamNonBlocking) == hipSuccess;
     for (int i = 0; ok && i < kSlots; ++i) ok = slot_init(slots[i], (size_t)w->max_batch, w->d, w->k);
     std::vector<int64_t> cands;
     for (int b = 1; b <= w->max_batch; b <<= 1) cands.push_back(b);
@@ -197,7 +184,7 @@ void worker_loop(ivf_worker* w) {
                 }
             }
             if (!s.batch.empty()) {
-                if ((fail_rc = slot_issue(w, s))) break;
+                if ((fail_rc = slot_issue(w, s, st))) break;
                 inflight += 1;
                 issued = true;
             }
@@ -240,6 +227,7 @@ void worker_loop(ivf_worker* w) {
         w->cv_res.notify_all();
     }
     (void)hipGetLastError();
+    if (st) { (void)hipStreamSynchronize(st); (void)hipStreamDestroy(st); }
     for (int i = 0; i < kSlots; ++i) slot_free(slots[i]);
 }
 

@@ -229,16 +229,17 @@ class Index:
         _check(self._lib.ivf_budget_wait(self._h))
 
     def search(self, queries, nprobe: int, k: int, out_ids=None, out_scores=None, stream=None):
-        """queries: float32 CUDA tensor [nq, d].  Returns (ids int64 [nq,k], scores
-        float32 [nq,k]) CUDA tensors; valid once `stream` (default: torch's current
-        stream) has been synchronised."""
+        """queries: float32 tensor [nq, d], CUDA or pinned host memory.  Returns (ids int64
+        [nq,k], scores float32 [nq,k]), CUDA tensors unless the caller passes its own (CUDA
+        or pinned); valid once `stream` (default: torch's current stream) has been
+        synchronised."""
         import torch
-        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        assert (queries.is_cuda or queries.is_pinned()) and queries.dtype == torch.float32 and queries.is_contiguous()
         nq = queries.shape[0]
         if out_ids is None:
-            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
         if out_scores is None:
-            out_scores = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+            out_scores = torch.empty((nq, k), dtype=torch.float32, device="cuda")
         _check(self._lib.ivf_search(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
                                     _ptr(out_scores), _stream_handle(stream)))
         return out_ids, out_scores
@@ -248,12 +249,12 @@ class Index:
         """ivf_search_queued: as `search`, but `queries` is read as soon as `queries_ready`
         (a torch.cuda.Event, or None = now) allows, not behind earlier work on `stream`."""
         import torch
-        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        assert (queries.is_cuda or queries.is_pinned()) and queries.dtype == torch.float32 and queries.is_contiguous()
         nq = queries.shape[0]
         if out_ids is None:
-            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
         if out_scores is None:
-            out_scores = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+            out_scores = torch.empty((nq, k), dtype=torch.float32, device="cuda")
         ev = None if queries_ready is None else queries_ready.cuda_event
         _check(self._lib.ivf_search_queued(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),
                                            _ptr(out_scores), _stream_handle(stream), ev))
@@ -262,7 +263,7 @@ class Index:
     def search_noalloc(self, queries, nprobe: int, k: int, out_ids, out_scores, stream=None):
         """ivf_search_noalloc: the caller passes every buffer; the library allocates nothing."""
         import torch
-        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        assert (queries.is_cuda or queries.is_pinned()) and queries.dtype == torch.float32 and queries.is_contiguous()
         nq = queries.shape[0]
         assert tuple(out_ids.shape) == (nq, k) and tuple(out_scores.shape) == (nq, k)
         _check(self._lib.ivf_search_noalloc(self._h, _ptr(queries), nq, nprobe, k, _ptr(out_ids),

@@ -223,3 +223,38 @@ def test_first_queued_searches_on_a_busy_stream():
             assert np.array_equal(sc.cpu().numpy(), refs[i % 3][1]), f"search {i}"
     finally:
         idx.close()
+
+
+def test_queries_and_results_in_pinned_host_memory(c1):
+    """Queries handed over in pinned host memory are copied to the device by the search
+    itself (on the stream of its first kernel), results may land in pinned host memory
+    directly: same rows as with device buffers, for plain, queued and no-allocation
+    searches; pageable host memory is refused."""
+    import torch
+    w, h, idx = c1
+    qs, qd, refs = _refs(idx, w, 3)
+    qp = [torch.from_numpy(q).pin_memory() for q in qs]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    say("C1: pinned queries -> plain, queued (pinned results), no-allocation searches")
+    for b in range(3):
+        ids, sc = idx.search(qp[b], w.nprobe, w.k, stream=st)
+        st.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), refs[b][0]) and np.array_equal(sc.cpu().numpy(), refs[b][1])
+    outs = []
+    for i in range(12):
+        hi = torch.full((w.nq, w.k), -7, dtype=torch.int64).pin_memory()
+        hs = torch.full((w.nq, w.k), np.nan, dtype=torch.float32).pin_memory()
+        idx.search_queued(qp[i % 3], w.nprobe, w.k, hi, hs, stream=st)
+        outs.append((hi, hs))
+    st.synchronize()
+    for i, (hi, hs) in enumerate(outs):
+        assert np.array_equal(hi.numpy(), refs[i % 3][0]) and np.array_equal(hs.numpy(), refs[i % 3][1]), f"search {i}"
+    di = torch.empty((w.nq, w.k), dtype=torch.int64, device="cuda")
+    ds = torch.empty((w.nq, w.k), dtype=torch.float32, device="cuda")
+    idx.search_noalloc(qp[1], w.nprobe, w.k, di, ds, stream=st)
+    st.synchronize()
+    assert np.array_equal(di.cpu().numpy(), refs[1][0]) and np.array_equal(ds.cpu().numpy(), refs[1][1])
+    pageable = np.ascontiguousarray(qs[0])
+    rc = idx._lib.ivf_search(idx._h, pageable.ctypes.data, w.nq, w.nprobe, w.k, di.data_ptr(), ds.data_ptr(), None)
+    assert rc == -1 and b"pinned" in idx._lib.ivf_last_error()      # IVF_ERR_INVALID
