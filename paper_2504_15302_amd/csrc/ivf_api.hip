@@ -638,13 +638,16 @@ void enqueue_scan(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) 
 
 void enqueue_scan_kernels(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t st) {
     if (x->dtype == IVF_PQ8) {
-        // product-quantised lists: the queries' tables against the codebooks, then one
-        // workgroup per (query, list) pair gathers from its query's table in LDS
+        // product-quantised lists: the queries' tables against the codebooks, then workgroups
+        // that hold one query's table in LDS and scan a share of its probed lists: enough
+        // shares for about four workgroups per compute unit, at most kPqWgLists lists each
         hipLaunchKernelGGL(k_pq_tables, dim3((unsigned)x->pq_m, (unsigned)c.nq), dim3(256), 0, st, c.Q, x->d_codebooks,
                            s.pq_tables, x->d, x->pq_m);
-        hipLaunchKernelGGL(k_pq_scan, dim3((unsigned)c.npairs), dim3(kPqThreads), (size_t)x->pq_m * 1024, st, s.pair_flat,
-                           s.probes, s.pair_start, s.sblk_start, x->d_nblk, x->d_len, x->d_list_ptr, c.nprobe, x->pq_m,
-                           s.pq_tables, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
+        const int64_t fewest = (c.nprobe + kPqWgLists - 1) / kPqWgLists;
+        const int64_t parts = std::min<int64_t>(c.nprobe, std::max<int64_t>(fewest, (1024 + c.nq - 1) / c.nq));
+        hipLaunchKernelGGL(k_pq_scan, dim3((unsigned)parts, (unsigned)c.nq), dim3(kPqThreads), (size_t)x->pq_m * 1024, st,
+                           s.probes, s.pair_of_probe, s.pair_start, s.sblk_start, x->d_nblk, x->d_len, x->d_list_ptr, c.nprobe,
+                           x->pq_m, s.pq_tables, s.scores, s.bmax, s.qthr, c.prune_blocks, c.prune_j);
         return;
     }
     if (x->resident_lists > 0 || x->opt_host_direct) {
