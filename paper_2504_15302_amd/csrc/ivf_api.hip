@@ -546,7 +546,11 @@ int search_prologue(ivf_index* x, hipStream_t st, SearchCtx& c) {
 // of work items, where nothing has a bound to prune by yet.
 void search_set_pruning(const ivf_index* x, SearchCtx& c) {
     const bool small_plan = x->opt_scan_prune != 2 && block_bound(x, c.nq, c.nprobe) < 32768;
-    if (!x->opt_scan_prune || c.k > 128 || small_plan) { c.prune_blocks = 0; c.prune_j = 0; }
+    // Over product-quantisation codes a wavefront scans block after block, and the bound
+    // costs it more at every block (half as much again at 100 M vectors) than the stores
+    // it saves: no pruning there unless asked for ("scan_prune" = 2).
+    const bool pq_default = x->dtype == IVF_PQ8 && x->opt_scan_prune != 2;
+    if (!x->opt_scan_prune || c.k > 128 || small_plan || pq_default) { c.prune_blocks = 0; c.prune_j = 0; }
     else if (c.k <= 64) { c.prune_blocks = 1; c.prune_j = c.k; }
     else { c.prune_blocks = 2; c.prune_j = (c.k + 1) / 2; }
 }

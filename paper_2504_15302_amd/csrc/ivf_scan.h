@@ -207,10 +207,14 @@ __device__ __forceinline__ void scan_finish(const ScanItem& it, int d, const flo
                     store = false;                 // nothing here can enter the top-k
                 } else {
                     const uint32_t o = valid ? ord_of(s) : 0u;
-                    uint32_t t = 0;                // j-th largest of the block, bit by bit
-                    for (int bit = 31; bit >= 0; --bit) {
-                        const uint32_t cand = t | (1u << bit);
-                        if (__popcll(__ballot(o >= cand)) >= prune_j) t = cand;
+                    uint32_t t = 0;                // j-th largest of the block, bit by bit; only its
+                                                   // excess over the bound matters, and it exceeds
+                                                   // the bound only if j scores of the block do
+                    if (__popcll(__ballot(o > thr)) >= prune_j) {
+                        for (int bit = 31; bit >= 0; --bit) {
+                            const uint32_t cand = t | (1u << bit);
+                            if (__popcll(__ballot(o >= cand)) >= prune_j) t = cand;
+                        }
                     }
                     if (t > thr && lane == 0) {
                         if (prune_blocks == 1) {
