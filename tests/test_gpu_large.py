@@ -179,6 +179,20 @@ def test_c5_full_size_every_row_matches_oracle():
     res = check_large(dw, q, w.nprobe, w.k, got)
     assert res["queries"] == w.nq
     say(f"C5 ok on all {w.nq} rows: {res}")
+    # the launch configuration that bench.py times: searches queued back to back on a stream
+    # of the caller's, stages of neighbours overlapping; rows are those of the plain search
+    import torch
+    say("C5: six queued searches over two batches")
+    q2 = W.queries(w, batch=1)
+    got2 = gpu_search(dw.index, q2, w.nprobe, w.k)
+    qd = [torch.from_numpy(q).cuda(), torch.from_numpy(q2).cuda()]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = [dw.index.search_queued(qd[i % 2], w.nprobe, w.k, stream=st) for i in range(6)]
+    st.synchronize()
+    for i, (ids, sc) in enumerate(outs):
+        ref = got if i % 2 == 0 else got2
+        assert np.array_equal(ids.cpu().numpy(), ref[0]) and np.array_equal(sc.cpu().numpy(), ref[1]), f"queued search {i}"
     # half the batch: the coarse kernel then runs its 64-row tile
     say("C5: search nq=64 nprobe=16 k=10")
     got = gpu_search(dw.index, q[:64], 16, 10)
