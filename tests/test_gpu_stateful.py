@@ -61,11 +61,45 @@ def test_random_walk_over_the_library_state(seed, storage):
         refs.append(got)
     direct, log = 1, []
 
+    import torch
+    idx.set_option("queue_min_mb", 0)                         # queued searches overlap however small they are
+    own = torch.cuda.Stream()
+    q_dev = [torch.from_numpy(q).cuda() for q in queries]
+    q_pin = [torch.from_numpy(q).pin_memory() for q in queries]
+
     def search(i):
+        """One of the entry points, by lot: plain; two queued searches back to back on a stream of
+        the test's; queued with queries and results in pinned host memory; no allocation (refused
+        during a budget change and in the staged mode: then plain)."""
         nq, nprobe, k = shapes[i]
-        got = gpu_search(idx, queries[i], nprobe, k)
-        assert np.array_equal(got[0], refs[i][0]) and np.array_equal(got[1], refs[i][1]), \
-            f"shape {shapes[i]} changed after: {log[-12:]}"
+        mode = int(rng.integers(0, 4))
+        log[-1] += "/" + ("plain", "queued", "pinned", "noalloc")[mode]
+        if mode == 1:
+            outs = [idx.search_queued(q_dev[i], nprobe, k, stream=own) for _ in range(2)]
+            own.synchronize()
+            got = [(a.cpu().numpy(), b.cpu().numpy()) for a, b in outs]
+        elif mode == 2:
+            hi = torch.full((nq, k), -7, dtype=torch.int64).pin_memory()
+            hs = torch.full((nq, k), np.nan, dtype=torch.float32).pin_memory()
+            idx.search_queued(q_pin[i], nprobe, k, hi, hs, stream=own)
+            own.synchronize()
+            got = [(hi.numpy(), hs.numpy())]
+        else:
+            got = None
+            if mode == 3:
+                di = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+                ds = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+                try:
+                    idx.search_noalloc(q_dev[i], nprobe, k, di, ds, stream=own)
+                    own.synchronize()
+                    got = [(di.cpu().numpy(), ds.cpu().numpy())]
+                except ivf.IvfError as e:
+                    assert "budget change" in str(e) or "staged" in str(e), str(e)
+            if got is None:
+                got = [gpu_search(idx, queries[i], nprobe, k)]
+        for g in got:
+            assert np.array_equal(g[0], refs[i][0]) and np.array_equal(g[1], refs[i][1]), \
+                f"shape {shapes[i]} changed after: {log[-12:]}"
 
     for step in range(300):
         op = int(rng.integers(0, 100))
@@ -120,6 +154,7 @@ def test_random_walk_over_the_library_state(seed, storage):
                 f"list {l} damaged after: {log[-12:]}"
     idx.budget_wait()
     for i in range(len(shapes)):
+        log.append(f"search{i}")
         search(i)
     say(f"random walk seed {seed} ({storage}): {len(log)} operations, last: {log[-6:]}")
     idx.close()
