@@ -1216,32 +1216,31 @@ int pick_pipe_streams(ivf_index* x, hipStream_t st) {
         if (!x->ev_trial[i]) HIP_TRY(hipEventCreate(&x->ev_trial[i]));
     // earlier searches may still run on streams made before: trials need them idle
     HIP_TRY(hipDeviceSynchronize());
-    std::vector<hipStream_t> picked, spare;
+    std::vector<hipStream_t> picked, spare, tried;
     for (hipStream_t s : {x->pipe_front[0], x->pipe_front[1], x->pipe_scan})
         if (s) spare.push_back(s);               // made by a call that could not run the trials
     x->pipe_front[0] = x->pipe_front[1] = x->pipe_scan = nullptr;
-    std::vector<hipStream_t> tried;
-    for (int n = 0; n < 12 && picked.size() < 3; ++n) {
+    int rc_trials = 0;
+    for (int n = 0; n < 12 && picked.size() < 3 && !rc_trials; ++n) {
         hipStream_t c = nullptr;
         if (!spare.empty()) { c = spare.back(); spare.pop_back(); }
-        else if ((rc = need_stream(c))) return rc;
+        else if ((rc_trials = need_stream(c))) break;
         bool ok = true;
-        if ((rc = streams_run_side_by_side(x, st, c, ok))) return rc;
-        for (size_t i = 0; ok && i < picked.size(); ++i)
-            if ((rc = streams_run_side_by_side(x, picked[i], c, ok))) return rc;
-        (ok ? picked : tried).push_back(c);
+        rc_trials = streams_run_side_by_side(x, st, c, ok);
+        for (size_t i = 0; !rc_trials && ok && i < picked.size(); ++i)
+            rc_trials = streams_run_side_by_side(x, picked[i], c, ok);
+        (ok && !rc_trials ? picked : tried).push_back(c);
     }
+    // whatever happened, the index ends up owning three streams (or as many as could be
+    // made) and nothing else
     for (hipStream_t s : spare) tried.push_back(s);
-    while (picked.size() < 3) {
-        hipStream_t c = nullptr;
-        if (!tried.empty()) { c = tried.back(); tried.pop_back(); }
-        else if ((rc = need_stream(c))) return rc;
-        picked.push_back(c);
-    }
+    while (picked.size() < 3 && !tried.empty()) { picked.push_back(tried.back()); tried.pop_back(); }
     for (hipStream_t s : tried) (void)hipStreamDestroy(s);
-    x->pipe_scan = picked[0];
-    x->pipe_front[0] = picked[1];
-    x->pipe_front[1] = picked[2];
+    hipStream_t* slots[3] = {&x->pipe_scan, &x->pipe_front[0], &x->pipe_front[1]};
+    for (size_t i = 0; i < picked.size(); ++i) *slots[i] = picked[i];
+    if (rc_trials) return rc_trials;
+    for (hipStream_t* s : slots)
+        if ((rc = need_stream(*s))) return rc;
     x->pipe_picked = true;
     x->pipe_caller = st;
     return 0;
