@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # scaled against the library's plain copy kernel), and the summary each comes from.
 # Workloads that have not been counted report null.
 TRAFFIC_BYTES = {"C5": 1.66754e7 * 2.000 * 1024 + 8283.61 * 1024,
-                 "C5-int8": 8.38722e6 * 2.000 * 1024 + 5468.62 * 1024}
+                 "C5-int8": 8.38864e6 * 2.000 * 1024 + 5432.68 * 1024}
 TRAFFIC_SOURCE = {"C5": "profiles/k_scan_C5_pmc_traffic.md",
                   "C5-int8": "profiles/k_scan_C5_int8_trace_and_traffic.md"}
 

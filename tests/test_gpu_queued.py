@@ -1,5 +1,5 @@
 """Searches queued back to back: ivf_search_queued overlaps the stages of neighbouring
-searches on the library's own streams and two sets of scratch memory, and consecutive
+searches on the library's own streams and three sets of scratch memory, and consecutive
 searches of one index may be issued on different streams.  Rows must be bit-identical to
 those of ivf_search issued one by one (results never depend on batching or scheduling:
 paper Section 6.1 "Key Metrics")."""
