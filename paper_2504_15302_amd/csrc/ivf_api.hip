@@ -435,9 +435,10 @@ int stream_host_lists(ivf_index* x, Scratch& s, const SearchCtx& c, hipStream_t 
                         it.q[jq] = (uint16_t)(pl[h.first + g * kQB + std::min(jq, nqg - 1)].second / (uint32_t)nprobe);
                     it.nq = (uint16_t)nqg;
                     it.nvalid = (uint16_t)std::min<uint32_t>(64u, (uint32_t)x->len[h.l] - b * 64u);
-                    it.pad = 0;
-                    s.h_items[item_off++] = it;
+                    it.shared = groups > 1 ? 1u : 0u;
+                    s.h_items[item_off + item_slot(g, b, groups)] = it;
                 }
+            item_off += (size_t)groups * nb;
             loff += (size_t)nb * x->block_bytes;
         }
         const size_t nitems = item_off - item_begin;

@@ -22,9 +22,18 @@ struct ScanItem {
     uint16_t q[kQB];    // query rows of the group (entries past nq repeat the last one)
     uint16_t nq;        // queries in the group, 1..kQB
     uint16_t nvalid;    // valid vectors in the block, 1..64
-    uint32_t pad;
+    uint32_t shared;    // 1: other groups of queries read the same block (the list has more than kQB probes)
 };
 static_assert(sizeof(ScanItem) == 32, "ScanItem layout");
+
+// Place of the item (group g of queries, block b) among the items of a list that `groups`
+// groups of queries probe: the groups that read the same block are neighbours, so they run
+// in the same or in neighbouring workgroups at about the same time and, reading with plain
+// loads, find part of the block in the caches (what a nontemporal load brings in is not
+// kept).  With one group the place is b.
+__host__ __device__ inline unsigned item_slot(unsigned g, unsigned b, unsigned groups) {
+    return b * groups + g;
+}
 
 // Monotone map float -> uint32 (larger score <=> larger key); -0 and +0 coincide.
 __device__ __forceinline__ uint32_t ord_of(float s) {

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kPqThreads) void k_pq_scan(
         it.q[0] = it.q[1] = it.q[2] = it.q[3] = (uint16_t)q;
         it.nq = 1;
         it.nvalid = (uint16_t)min(64, l_len[ci] - cb * 64);
-        it.pad = 0;
+        it.shared = 0;
         scan_finish<kF32, 1>(it, 0, acc, scores, bmax, lane, qthr, prune_blocks, prune_j);
         if (gn < total) {
 #pragma unroll

@@ -202,8 +202,8 @@ __global__ void k_plan(const int* __restrict__ hist, const int32_t* __restrict__
                 it.q[j] = (uint16_t)(seg[g * kQB + min(j, nqg - 1)] / (uint32_t)nprobe);
             it.nq = (uint16_t)nqg;
             it.nvalid = (uint16_t)min(64u, ln - b * 64u);
-            it.pad = 0;
-            out[g * nb + b] = it;
+            it.shared = groups > 1 ? 1u : 0u;
+            out[item_slot(g, b, groups)] = it;
         }
     }
 }
@@ -338,8 +338,8 @@ __global__ __launch_bounds__(T) void k_regroup_small(
                     it.q[j] = (uint16_t)(seg[g * kQB + min(j, nqg - 1)] / (uint32_t)nprobe);
                 it.nq = (uint16_t)nqg;
                 it.nvalid = (uint16_t)min(64u, ln - b * 64u);
-                it.pad = 0;
-                out[g * nb + b] = it;
+                it.shared = groups > 1 ? 1u : 0u;
+                out[item_slot(g, b, groups)] = it;
             }
         }
     }
