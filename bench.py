@@ -277,6 +277,34 @@ def measure(idx, w, steps, warmup, nb, direct=True, stages=True, components=None
     return rep, q_host, q_dev, first, (out_ids, out_scores)
 
 
+def worker_report(idx, w, q_host, first, log, batches=24):
+    """The retrieval worker over the same index (single requests in, batches formed by the
+    worker with the batch-size rule, rows out by ticket): requests per second under a backlog
+    of `batches` x nq requests, host queries and results in pinned memory (PCIe-inclusive)."""
+    import numpy as np
+    from paper_2504_15302_amd import ivf
+    nb = len(q_host)
+    wk = ivf.Worker(idx, w.nprobe, w.k, w.nq)
+    try:
+        for t in [wk.submit(q_host[0][i]) for i in range(w.nq)]:          # warm-up: one batch
+            wk.wait(t)
+        n = batches * w.nq
+        t0 = time.perf_counter()
+        tickets = [wk.submit(q_host[(i // w.nq) % nb][i % w.nq]) for i in range(n)]
+        got = [wk.wait(t) for t in tickets]
+        dt = time.perf_counter() - t0
+        st = wk.stats()
+        rows_ok = all(np.array_equal(got[i][0], first[0][i]) and np.array_equal(got[i][1], first[1][i])
+                      for i in range(w.nq))                              # the first nq requests are batch 0
+    finally:
+        wk.stop()
+    log(f"worker: {n / dt:.0f} queries/s over {n} single requests")
+    return {"queries_per_s": n / dt, "requests": n, "batches_formed": int(st.batches) - 1,
+            "largest_batch": int(st.largest_batch), "rows_of_batch_0_equal_plain_search": bool(rows_ok),
+            "note": "ivf_worker_*: requests submitted one by one from the host, queries and results in pinned "
+                    "host memory, batches formed by the worker; PCIe-inclusive"}
+
+
 def pcie_report(rep, direct, h2d):
     streamed = rep["_streamed"]
     # direct reads happen inside the scan; staged copies are a stage of their own (searches
@@ -479,6 +507,8 @@ def main():
         result["k_sweep_queries_per_s"] = sweep
     if args.budget_change:
         result["budget_change"] = budget_change(idx, w, lw, q_dev, out_ids, out_scores, first, log)
+    if not experiment and direct:
+        result["worker"] = worker_report(idx, w, q_host, first, log)
     if args.cpu_seconds > 0:
         log("timing the CPU oracle on a sample of batch 0")
         result["cpu_baseline"] = cpu_baseline(lw, q_host[0], first[0], first[1], w.nprobe, w.k, args.cpu_seconds)
