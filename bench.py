@@ -344,6 +344,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="0 skips the CPU baseline")
     ap.add_argument("--option", action="append", default=[], help="library option name=value")
     ap.add_argument("--n", type=int, default=0, help="override the number of vectors (experiments only)")
+    ap.add_argument("--uniform-list-len", type=int, default=0,
+                    help="experiment: every list of the workload exactly this many vectors long (n = nlist x length)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel over this many MiB (reference "
                          "point for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
@@ -375,7 +377,7 @@ def main():
     from paper_2504_15302_amd.loader import load_workload
 
     experiment = bool(args.option or args.n or args.batch_sweep or args.k_sweep or args.budget_change
-                      or args.calibrate_copy_mib or args.skew_components)
+                      or args.calibrate_copy_mib or args.skew_components or args.uniform_list_len)
     if args.others is None:
         others = ["C1", "C2", "C3", "C4"] if (args.workload == "C5" and not experiment) else []
     else:
@@ -384,6 +386,8 @@ def main():
     w = W.CONFIGS[args.workload]
     if args.n:
         w = W.scaled(w, n=args.n, name=w.name + f"-n{args.n}")
+    if args.uniform_list_len:
+        w = W.scaled(w, n=w.nlist * args.uniform_list_len, uniform_lists=True, name=w.name + f"-len{args.uniform_list_len}")
     log(f"building {w.name}: {w.n} x {w.d} {w.storage}, nlist {w.nlist}")
     lw = load_workload(w, groups_per_chunk=32, log=log)
     idx = lw.index

@@ -58,6 +58,7 @@ class Workload:
     seed: int
     resident_list_frac: Optional[float] = None  # None = everything HBM-resident
     pq_m: int = 0         # "pq8": number of subspaces (one byte of code each)
+    uniform_lists: bool = False   # every list n / nlist vectors long (experiments on the effect of list length)
 
     @property
     def elem_bytes(self) -> int:
@@ -121,7 +122,11 @@ def centroids(w: Workload) -> np.ndarray:
 
 def list_offsets(w: Workload) -> np.ndarray:
     """[nlist+1] int64 prefix sums of the multinomial list sizes."""
-    sizes = _rng(w, _STREAM_SIZES).multinomial(w.n, np.full(w.nlist, 1.0 / w.nlist))
+    if w.uniform_lists:
+        assert w.n % w.nlist == 0
+        sizes = np.full(w.nlist, w.n // w.nlist, dtype=np.int64)
+    else:
+        sizes = _rng(w, _STREAM_SIZES).multinomial(w.n, np.full(w.nlist, 1.0 / w.nlist))
     off = np.zeros(w.nlist + 1, dtype=np.int64)
     np.cumsum(sizes, out=off[1:])
     return off
