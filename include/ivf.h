@@ -369,7 +369,8 @@ int ivf_debug_read(const void *src, int64_t bytes, void *sink, void *stream);
    added in LDS, so scores may differ in the last bit between settings), "queue_min_mb" (see
    ivf_search_queued), "queue_fronts" 0|1|2 (streams that the front stages of queued searches
    alternate between; 0 = two behind short scans, one behind long ones),
-   "scan_prune" 0|1|2 (store pruning off / on for large plans / always),
+   "scan_prune" 0|1|2 (store pruning off / on for large plans of flat and int8 lists / always, also
+   over product-quantisation codes, where it costs more than it saves),
    "regroup_fused" 0|1 (1 = searches with at most 1024 lists and 2048 (query, list) pairs
    regroup in a single launch), "sel_threads" 0|256|1024 (workgroup size of the selection kernels; 0 = by problem size),
    "residency_policy" 0|1 and "segment_mb" (see ivf_set_device_budget; the segment size
